@@ -1,0 +1,273 @@
+"""Thin ctypes binding over libapnn.so: argument marshalling only.
+
+Every function has the name of the C entry point it calls (``include/apnn.h``);
+tensors are PyTorch device tensors used purely as device memory, the stream is
+PyTorch's current stream.  No computation of the method happens in Python.
+The library must have been built (``python -m paper_2106_12169_amd.build``);
+a missing library is an error, there is no fallback path.
+"""
+
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+ENC_UNSIGNED, ENC_PM1 = 0, 1
+LAYOUT_NHWC, LAYOUT_NCHW = 0, 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libapnn.so")
+
+EXPORTS = (
+    "apnn_last_error", "apnn_row_words", "apnn_packed_words", "apnn_fmap_words",
+    "apnn_pack", "apnn_pack_fmap", "apnn_pack_conv_weights", "apnn_pack_patches",
+    "apnn_pack_patch_weights", "apnn_quantize", "apnn_gemm", "apnn_conv2d", "apnn_layer",
+    "apnn_fold_bn", "apnn_maxpool", "apnn_sumpool", "apnn_probe_valu", "apnn_probe_copy",
+)
+
+
+class ApnnError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"apnn status {status}: {text}")
+        self.status = status
+
+
+class ConvDesc(C.Structure):
+    _fields_ = [("N", C.c_int64), ("H", C.c_int64), ("W", C.c_int64), ("Cin", C.c_int64), ("Cout", C.c_int64),
+                ("R", C.c_int), ("S", C.c_int), ("stride", C.c_int), ("pad", C.c_int),
+                ("p", C.c_int), ("q", C.c_int), ("encW", C.c_int), ("encX", C.c_int)]
+
+
+class LayerDesc(C.Structure):
+    _fields_ = [("conv", ConvDesc), ("is_gemm", C.c_int), ("q_out", C.c_int),
+                ("scale_dev", C.c_void_p), ("bias_dev", C.c_void_p),
+                ("residual_dev", C.c_void_p), ("q_res", C.c_int), ("res_scale", C.c_float),
+                ("acc_out_dev", C.c_void_p), ("float_out_dev", C.c_void_p)]
+
+
+_lib = None
+
+
+def lib():
+    """Load libapnn.so (once) and declare the prototypes of include/apnn.h."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2106_12169_amd.build`")
+    L = C.CDLL(LIB_PATH)
+    i64, i32, vp, f32 = C.c_int64, C.c_int, C.c_void_p, C.c_float
+    L.apnn_last_error.restype = C.c_char_p
+    L.apnn_row_words.restype = i64
+    L.apnn_row_words.argtypes = [i64]
+    L.apnn_packed_words.restype = C.c_size_t
+    L.apnn_packed_words.argtypes = [i64, i64, i32]
+    L.apnn_fmap_words.restype = C.c_size_t
+    L.apnn_fmap_words.argtypes = [i64, i64, i32]
+    L.apnn_pack.argtypes = [vp, i64, i64, i32, i32, vp, vp]
+    L.apnn_pack_fmap.argtypes = [vp, i32, i64, i64, i64, i64, i32, i32, vp, vp]
+    L.apnn_pack_conv_weights.argtypes = [vp, i64, i64, i32, i32, i32, i32, vp, vp]
+    L.apnn_pack_patches.argtypes = [vp, i64, i64, i64, i64, i32, i32, i32, i32, i32, vp, vp]
+    L.apnn_pack_patch_weights.argtypes = [vp, i64, i64, i32, i32, i32, i32, vp, vp]
+    L.apnn_quantize.argtypes = [vp, i64, i64, f32, f32, i32, vp, vp]
+    L.apnn_gemm.argtypes = [vp, vp, vp, i64, i64, i64, i32, i32, i32, i32, vp]
+    L.apnn_conv2d.argtypes = [C.POINTER(ConvDesc), vp, vp, vp, vp]
+    L.apnn_layer.argtypes = [C.POINTER(LayerDesc), vp, vp, vp, vp]
+    L.apnn_fold_bn.argtypes = [vp, vp, vp, vp, C.c_double, C.c_double, C.c_double, i64, vp, vp]
+    L.apnn_maxpool.argtypes = [vp, i64, i64, i64, i64, i32, i32, i32, i32, vp, vp]
+    L.apnn_sumpool.argtypes = [vp, i64, i64, i64, i64, i32, i32, vp, vp]
+    L.apnn_probe_valu.argtypes = [i32, i32, vp, C.POINTER(C.c_double), vp]
+    L.apnn_probe_copy.argtypes = [vp, vp, C.c_size_t, vp]
+    for name in EXPORTS:
+        if name not in ("apnn_last_error", "apnn_row_words", "apnn_packed_words", "apnn_fmap_words"):
+            getattr(L, name).restype = i32
+    _lib = L
+    return L
+
+
+def _check(status: int):
+    if status != 0:
+        raise ApnnError(status, lib().apnn_last_error().decode())
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "device, contiguous tensors only"
+    return t.data_ptr()
+
+
+def _words(n: int, device) -> torch.Tensor:
+    # int32 storage for uint32 words; at least one element so data_ptr() is valid
+    return torch.empty(max(int(n), 1), dtype=torch.int32, device=device)
+
+
+def apnn_row_words(K: int) -> int:
+    return lib().apnn_row_words(K)
+
+
+def apnn_packed_words(rows: int, K: int, bits: int) -> int:
+    return lib().apnn_packed_words(rows, K, bits)
+
+
+def apnn_fmap_words(pixels: int, Cc: int, bits: int) -> int:
+    return lib().apnn_fmap_words(pixels, Cc, bits)
+
+
+def apnn_pack(src: torch.Tensor, bits: int, enc: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """src: rows x K uint8/int8 device tensor -> packed matrix operand (int32 words)."""
+    rows, K = src.shape
+    if out is None:
+        out = _words(apnn_packed_words(rows, K, bits), src.device)
+    _check(lib().apnn_pack(_ptr(src), rows, K, bits, enc, _ptr(out), _stream()))
+    return out
+
+
+def apnn_pack_fmap(src: torch.Tensor, layout: int, bits: int, enc: int,
+                   out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    if layout == LAYOUT_NHWC:
+        N, H, W, Cc = src.shape
+    else:
+        N, Cc, H, W = src.shape
+    if out is None:
+        out = _words(apnn_fmap_words(N * H * W, Cc, bits), src.device)
+    _check(lib().apnn_pack_fmap(_ptr(src), layout, N, H, W, Cc, bits, enc, _ptr(out), _stream()))
+    return out
+
+
+def apnn_pack_conv_weights(src: torch.Tensor, bits: int, enc: int) -> torch.Tensor:
+    Cout, Cin, R, S = src.shape
+    out = _words(Cout * bits * R * S * ((Cin + 31) // 32), src.device)
+    _check(lib().apnn_pack_conv_weights(_ptr(src), Cout, Cin, R, S, bits, enc, _ptr(out), _stream()))
+    return out
+
+
+def apnn_pack_patches(img: torch.Tensor, R: int, S: int, stride: int, pad: int, bits: int,
+                      out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    N, Cc, H, W = img.shape
+    Ho, Wo = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+    if out is None:
+        out = _words(apnn_packed_words(N * Ho * Wo, 32 * R, bits), img.device)
+    _check(lib().apnn_pack_patches(_ptr(img), N, Cc, H, W, R, S, stride, pad, bits, _ptr(out), _stream()))
+    return out
+
+
+def apnn_pack_patch_weights(src: torch.Tensor, bits: int, enc: int) -> torch.Tensor:
+    Cout, Cin, R, S = src.shape
+    out = _words(apnn_packed_words(Cout, 32 * R, bits), src.device)
+    _check(lib().apnn_pack_patch_weights(_ptr(src), Cout, Cin, R, S, bits, enc, _ptr(out), _stream()))
+    return out
+
+
+def apnn_quantize(src: torch.Tensor, zero: float, step: float, bits: int) -> torch.Tensor:
+    rows, K = src.shape
+    assert src.dtype == torch.float32
+    out = _words(apnn_packed_words(rows, K, bits), src.device)
+    _check(lib().apnn_quantize(_ptr(src), rows, K, zero, step, bits, _ptr(out), _stream()))
+    return out
+
+
+def apnn_gemm(W: torch.Tensor, X: torch.Tensor, M: int, N: int, K: int, p: int, q: int,
+              encW: int, encX: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.int32, device=W.device)
+    _check(lib().apnn_gemm(_ptr(W), _ptr(X), _ptr(out) if out.numel() else None, M, N, K, p, q, encW, encX, _stream()))
+    return out
+
+
+@dataclass
+class Conv:
+    """Plain description of a convolution (or, with is_gemm, a matrix layer)."""
+    N: int
+    H: int
+    W: int
+    Cin: int
+    Cout: int
+    R: int = 1
+    S: int = 1
+    stride: int = 1
+    pad: int = 0
+    p: int = 1
+    q: int = 2
+    encW: int = ENC_PM1
+    encX: int = ENC_UNSIGNED
+
+    @property
+    def Ho(self):
+        return (self.H + 2 * self.pad - self.R) // self.stride + 1
+
+    @property
+    def Wo(self):
+        return (self.W + 2 * self.pad - self.S) // self.stride + 1
+
+    def c(self) -> ConvDesc:
+        return ConvDesc(self.N, self.H, self.W, self.Cin, self.Cout, self.R, self.S, self.stride, self.pad,
+                        self.p, self.q, self.encW, self.encX)
+
+
+def apnn_conv2d(d: Conv, W: torch.Tensor, X: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    if out is None:
+        out = torch.empty((d.N, d.Ho, d.Wo, d.Cout), dtype=torch.int32, device=X.device)
+    desc = d.c()
+    _check(lib().apnn_conv2d(C.byref(desc), _ptr(W), _ptr(X), _ptr(out), _stream()))
+    return out
+
+
+def apnn_layer(d: Conv, W: torch.Tensor, X: torch.Tensor, *, is_gemm: bool = False, q_out: int = 0,
+               scale: Optional[torch.Tensor] = None, bias: Optional[torch.Tensor] = None,
+               residual: Optional[torch.Tensor] = None, q_res: int = 0, res_scale: float = 0.0,
+               acc_out: Optional[torch.Tensor] = None, float_out: Optional[torch.Tensor] = None,
+               out: Optional[torch.Tensor] = None) -> Optional[torch.Tensor]:
+    """Returns the packed output codes (or None when q_out == 0)."""
+    pixels = d.N * (1 if is_gemm else d.Ho * d.Wo)
+    if q_out > 0 and out is None:
+        out = _words(apnn_fmap_words(pixels, d.Cout, q_out), X.device)
+    L = LayerDesc(d.c(), int(is_gemm), q_out, _ptr(scale), _ptr(bias), _ptr(residual), q_res, res_scale,
+                  _ptr(acc_out), _ptr(float_out))
+    _check(lib().apnn_layer(C.byref(L), _ptr(W), _ptr(X), _ptr(out) if q_out > 0 else None, _stream()))
+    return out if q_out > 0 else None
+
+
+def apnn_maxpool(X: torch.Tensor, N: int, H: int, W: int, Cc: int, bits: int, k: int, stride: int, pad: int,
+                 out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    Ho, Wo = (H + 2 * pad - k) // stride + 1, (W + 2 * pad - k) // stride + 1
+    if out is None:
+        out = _words(apnn_fmap_words(N * Ho * Wo, Cc, bits), X.device)
+    _check(lib().apnn_maxpool(_ptr(X), N, H, W, Cc, bits, k, stride, pad, _ptr(out), _stream()))
+    return out
+
+
+def apnn_sumpool(X: torch.Tensor, N: int, H: int, W: int, Cc: int, bits: int, out_bits: int,
+                 out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    if out is None:
+        out = _words(apnn_packed_words(N, Cc, out_bits), X.device)
+    _check(lib().apnn_sumpool(_ptr(X), N, H, W, Cc, bits, out_bits, _ptr(out), _stream()))
+    return out
+
+
+def apnn_fold_bn(gamma, beta, mean, var, eps: float, zero: float, step: float):
+    """Host helper: numpy float64 arrays in, fp32 numpy (scale, bias) out."""
+    import numpy as np
+    g, b, m, v = (np.ascontiguousarray(a, np.float64) for a in (gamma, beta, mean, var))
+    scale, bias = np.empty(g.shape, np.float32), np.empty(g.shape, np.float32)
+    _check(lib().apnn_fold_bn(g.ctypes.data, b.ctypes.data, m.ctypes.data, v.ctypes.data, eps, zero, step,
+                              g.size, scale.ctypes.data, bias.ctypes.data))
+    return scale, bias
+
+
+def apnn_probe_valu(blocks: int, iters: int, out: torch.Tensor) -> float:
+    ops = C.c_double(0.0)
+    _check(lib().apnn_probe_valu(blocks, iters, _ptr(out), C.byref(ops), _stream()))
+    return ops.value
+
+
+def apnn_probe_copy(src: torch.Tensor, dst: torch.Tensor):
+    _check(lib().apnn_probe_copy(_ptr(src), _ptr(dst), src.numel() * src.element_size(), _stream()))

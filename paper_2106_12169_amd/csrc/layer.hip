@@ -1,0 +1,195 @@
+// Host side of apnn_gemm / apnn_conv2d / apnn_layer: argument validation,
+// encoding recovery constants (Sec. 3.2), tile choice (Sec. 4.3) and launch.
+#include <cstdlib>
+
+#include "common.h"
+#include "tile_launch.h"
+
+namespace apnn {
+
+// Tile choice in the spirit of Sec. 4.3: prefer the largest block tile (highest
+// compute intensity 2 bm bn / (bm + bn)) whose grid still gives every one of the
+// 256 compute units at least ~2 blocks; fall back to smaller tiles to recover
+// thread-level parallelism on small problems.
+static int pick_tile(int64_t M, int64_t N)
+{
+    if (const char *e = std::getenv("APNN_TILE")) {
+        const int r = std::atoi(e);
+        if (r == 8 || r == 4 || r == 2) return r;
+    }
+    auto blocks = [&](int r) { return ceil_div(M, 16 * r) * ceil_div(N, 16 * r); };
+    if (blocks(8) >= 512) return 8;
+    if (blocks(4) >= 384) return 4;
+    if (blocks(8) >= 256) return 8;
+    if (blocks(4) >= 192) return 4;
+    return 2;
+}
+
+struct Problem {
+    const char *who;
+    bool conv;
+    int64_t M, N, Ktotal;      // rows, columns, logical reduction length
+    int PA, PB;
+    apnn_encoding encA, encB;
+};
+
+static int run_tile(const Problem &pr, TileParams &p, int vw, void *stream)
+{
+    bool use_xor = false;
+    p.alpha = 1; p.uA = 0; p.uB = 0; p.c0 = 0;
+    const bool a_pm = pr.encA == APNN_ENC_PM1, b_pm = pr.encB == APNN_ENC_PM1;
+    if (a_pm && b_pm) {                 // Case II:  K - 2 popc(XOR)
+        if (pr.conv) return fail(APNN_ERR_UNSUPPORTED, "%s: -1/+1 weights with -1/+1 features is not implemented for convolution", pr.who);
+        use_xor = true; p.alpha = -2; p.c0 = static_cast<int>(pr.Ktotal);
+    } else if (a_pm) {                  // Case III: 2 What X - J X, J X = row sum of the 0/1 operand
+        p.alpha = 2; p.uB = -1;
+    } else if (b_pm) {
+        p.alpha = 2; p.uA = -1;
+    }
+    const int r = pick_tile(pr.M, pr.N);
+    const int64_t tiles = ceil_div(pr.M, 16 * r) * ceil_div(pr.N, 16 * r);
+    if (tiles > 0x7FFFFFFF) return fail(APNN_ERR_INVALID_ARG, "%s: problem too large for one launch", pr.who);
+    p.xcd_remap = (tiles % 8 == 0 && tiles >= 16) ? 1 : 0;
+    p.nk = static_cast<int>(ceil_div(p.Kw, kTileKC));
+    const unsigned grid = static_cast<unsigned>(tiles);
+    bool ok = false;
+    switch (r) {
+        case 8: ok = launch_tile8(p, pr.conv, vw, use_xor, grid, as_stream(stream)); break;
+        case 4: ok = launch_tile4(p, pr.conv, vw, use_xor, grid, as_stream(stream)); break;
+        default: ok = launch_tile2(p, pr.conv, vw, use_xor, grid, as_stream(stream)); break;
+    }
+    if (!ok) return fail(APNN_ERR_UNSUPPORTED, "%s: no kernel instance for this configuration", pr.who);
+    return check_launch(pr.who);
+}
+
+static int check_desc(const char *who, const apnn_conv_desc &d, bool is_gemm)
+{
+    if (int rc = check_bits_enc(who, "weight", d.p, d.encW)) return rc;
+    if (int rc = check_bits_enc(who, "activation", d.q, d.encX)) return rc;
+    if (d.N < 0 || d.Cin < 0 || d.Cout < 0) return fail(APNN_ERR_INVALID_ARG, "%s: negative size", who);
+    if (is_gemm) {
+        if (d.H != 1 || d.W != 1 || d.R != 1 || d.S != 1 || d.stride != 1 || d.pad != 0)
+            return fail(APNN_ERR_INVALID_ARG, "%s: is_gemm needs H = W = R = S = stride = 1, pad = 0", who);
+        return check_int32_range(who, d.Cin, d.p, d.q);
+    }
+    if (d.H < 1 || d.W < 1 || d.R < 1 || d.S < 1 || d.stride < 1 || d.pad < 0)
+        return fail(APNN_ERR_INVALID_ARG, "%s: bad convolution geometry", who);
+    if (d.H + 2 * d.pad < d.R || d.W + 2 * d.pad < d.S)
+        return fail(APNN_ERR_INVALID_ARG, "%s: kernel larger than the padded frame", who);
+    if (d.Cin % 32 != 0 || d.Cin == 0)
+        return fail(APNN_ERR_INVALID_ARG, "%s: Cin = %lld must be a positive multiple of 32 for packed features", who, (long long)d.Cin);
+    return check_int32_range(who, d.Cin * d.R * d.S, d.p, d.q);
+}
+
+static int layer_impl(const char *who, const apnn_layer_desc &L, const uint32_t *W_dev, const uint32_t *X_dev,
+                      uint32_t *out_packed, void *stream)
+{
+    const apnn_conv_desc &d = L.conv;
+    const bool is_gemm = L.is_gemm != 0;
+    if (int rc = check_desc(who, d, is_gemm)) return rc;
+    if (L.q_out < 0 || L.q_out > 8) return fail(APNN_ERR_UNSUPPORTED, "%s: q_out = %d, supported 0..8", who, L.q_out);
+    const bool want_float = L.q_out > 0 || L.float_out_dev != nullptr;
+    if (want_float && (!L.scale_dev || !L.bias_dev)) return fail(APNN_ERR_INVALID_ARG, "%s: scale_dev/bias_dev required", who);
+    if (L.q_out > 0 && !out_packed) return fail(APNN_ERR_INVALID_ARG, "%s: out_packed_dev is null but q_out > 0", who);
+    if (L.q_out > 0 && d.Cout % 32 != 0)
+        return fail(APNN_ERR_INVALID_ARG, "%s: Cout = %lld must be a multiple of 32 for packed output", who, (long long)d.Cout);
+    if (L.q_out == 0 && !L.acc_out_dev && !L.float_out_dev) return fail(APNN_ERR_INVALID_ARG, "%s: no output requested", who);
+    if (L.residual_dev) {
+        if (!want_float) return fail(APNN_ERR_INVALID_ARG, "%s: residual needs the scale/bias epilogue", who);
+        if (L.q_res < 1 || L.q_res > 8) return fail(APNN_ERR_UNSUPPORTED, "%s: q_res = %d, supported 1..8", who, L.q_res);
+        if (d.Cout % 32 != 0) return fail(APNN_ERR_INVALID_ARG, "%s: residual needs Cout multiple of 32", who);
+        if (!aligned16(L.residual_dev)) return fail(APNN_ERR_ALIGNMENT, "%s: residual_dev not 16-byte aligned", who);
+    }
+    int Ho = 1, Wo = 1;
+    if (!is_gemm) {
+        Ho = static_cast<int>((d.H + 2 * d.pad - d.R) / d.stride + 1);
+        Wo = static_cast<int>((d.W + 2 * d.pad - d.S) / d.stride + 1);
+    }
+    const int64_t M = d.N * Ho * Wo, N = d.Cout;
+    if (M > 0x7FFFFFFF || N > 0x7FFFFFFF || d.N * d.H * d.W > 0x7FFFFFFF)
+        return fail(APNN_ERR_INVALID_ARG, "%s: dimension exceeds 2^31", who);
+    if (M == 0 || N == 0) return APNN_OK;
+    if (d.Cin > 0 && (!W_dev || !X_dev)) return fail(APNN_ERR_INVALID_ARG, "%s: null operand", who);
+    if (!aligned16(W_dev) || !aligned16(X_dev)) return fail(APNN_ERR_ALIGNMENT, "%s: packed operands must be 16-byte aligned", who);
+    if ((out_packed && !aligned16(out_packed)) || (L.acc_out_dev && !aligned16(L.acc_out_dev)))
+        return fail(APNN_ERR_ALIGNMENT, "%s: outputs must be 16-byte aligned", who);
+
+    TileParams p{};
+    p.A = X_dev; p.B = W_dev;                 // activations supply the rows, weights the columns
+    p.M = static_cast<int>(M); p.N = static_cast<int>(N);
+    p.PA = d.q; p.PB = d.p;
+    int vw = 4;
+    if (is_gemm) {
+        p.Kw = static_cast<int>(apnn_row_words(d.Cin));
+        p.ldwA = p.ldwB = p.Kw;
+    } else {
+        const int64_t Cw = d.Cin / 32, Kw = Cw * d.R * d.S;
+        if (Kw > 0x7FFFFFFF) return fail(APNN_ERR_INVALID_ARG, "%s: K too large", who);
+        p.Cw = static_cast<int>(Cw); p.Kw = static_cast<int>(Kw);
+        p.ldwA = 0; p.ldwB = p.Kw;
+        p.H = static_cast<int>(d.H); p.W = static_cast<int>(d.W); p.R = d.R; p.S = d.S;
+        p.stride = d.stride; p.pad = d.pad; p.Ho = Ho; p.Wo = Wo;
+        p.invCw = 1.0f / static_cast<float>(Cw);
+        vw = (Cw % 4 == 0) ? 4 : (Cw % 2 == 0) ? 2 : 1;
+    }
+    p.Y = L.acc_out_dev;
+    if (want_float) {
+        p.scale = L.scale_dev; p.bias = L.bias_dev; p.T = L.float_out_dev;
+        p.res = L.residual_dev; p.q_res = L.q_res; p.res_scale = L.res_scale;
+        p.out = L.q_out > 0 ? out_packed : nullptr; p.q_out = L.q_out;
+    }
+    p.NW = static_cast<int>(N / 32);
+    Problem pr{who, !is_gemm, M, N, is_gemm ? d.Cin : d.Cin * d.R * d.S, p.PA, p.PB, d.encX, d.encW};
+    return run_tile(pr, p, vw, stream);
+}
+
+}  // namespace apnn
+
+using namespace apnn;
+
+extern "C" int apnn_gemm(const uint32_t *W_dev, const uint32_t *X_dev, int32_t *Y_dev, int64_t M, int64_t N,
+                         int64_t K, int p, int q, apnn_encoding encW, apnn_encoding encX, void *stream)
+{
+    clear_error();
+    if (int rc = check_bits_enc("apnn_gemm", "weight", p, encW)) return rc;
+    if (int rc = check_bits_enc("apnn_gemm", "activation", q, encX)) return rc;
+    if (M < 0 || N < 0 || K < 0) return fail(APNN_ERR_INVALID_ARG, "apnn_gemm: negative size");
+    if (M > 0x7FFFFFFF || N > 0x7FFFFFFF || apnn_row_words(K) > 0x7FFFFFFF)
+        return fail(APNN_ERR_INVALID_ARG, "apnn_gemm: dimension exceeds 2^31");
+    if (int rc = check_int32_range("apnn_gemm", K, p, q)) return rc;
+    if (M == 0 || N == 0) return APNN_OK;
+    if (!Y_dev) return fail(APNN_ERR_INVALID_ARG, "apnn_gemm: Y_dev is null");
+    if (K > 0 && (!W_dev || !X_dev)) return fail(APNN_ERR_INVALID_ARG, "apnn_gemm: null operand");
+    if (!aligned16(W_dev) || !aligned16(X_dev) || !aligned16(Y_dev))
+        return fail(APNN_ERR_ALIGNMENT, "apnn_gemm: buffers must be 16-byte aligned");
+    TileParams t{};
+    t.A = W_dev; t.B = X_dev;                 // weights supply the rows of Y (W is M x K, Sec. 4.1)
+    t.M = static_cast<int>(M); t.N = static_cast<int>(N);
+    t.PA = p; t.PB = q;
+    t.Kw = static_cast<int>(apnn_row_words(K));
+    t.ldwA = t.ldwB = t.Kw;
+    t.Y = Y_dev;
+    t.NW = static_cast<int>(N / 32);
+    Problem pr{"apnn_gemm", false, M, N, K, p, q, encW, encX};
+    return run_tile(pr, t, 4, stream);
+}
+
+extern "C" int apnn_conv2d(const apnn_conv_desc *desc, const uint32_t *W_dev, const uint32_t *X_dev, int32_t *Y_dev,
+                           void *stream)
+{
+    clear_error();
+    if (!desc) return fail(APNN_ERR_INVALID_ARG, "apnn_conv2d: desc is null");
+    if (!Y_dev) return fail(APNN_ERR_INVALID_ARG, "apnn_conv2d: Y_dev is null");
+    apnn_layer_desc L{};
+    L.conv = *desc;
+    L.acc_out_dev = Y_dev;
+    return layer_impl("apnn_conv2d", L, W_dev, X_dev, nullptr, stream);
+}
+
+extern "C" int apnn_layer(const apnn_layer_desc *desc, const uint32_t *W_dev, const uint32_t *X_dev,
+                          uint32_t *out_packed_dev, void *stream)
+{
+    clear_error();
+    if (!desc) return fail(APNN_ERR_INVALID_ARG, "apnn_layer: desc is null");
+    return layer_impl("apnn_layer", *desc, W_dev, X_dev, out_packed_dev, stream);
+}

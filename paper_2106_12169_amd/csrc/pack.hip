@@ -1,0 +1,308 @@
+// Bit decomposition and packing kernels (Sec. 3.1 Eq. 2; channel-major
+// organisation of Sec. 4.2 (a); quantisation layer of Sec. 5.2).
+//
+// One thread produces the 32-bit word(s) of one (row, k-word) position for all
+// planes: it reads 32 source values, takes bit t of each (Eq. 2) and gathers
+// them LSB-first into the word of plane t.  The work is HBM-bound: rows*K bytes
+// in, rows*K*bits/8 bytes out.
+#include "common.h"
+
+namespace apnn {
+
+// 4 bytes holding 0/1 each -> 4-bit number, byte 0 in bit 0.  The multiplier
+// places byte i at bit 24+i; the stray partial products all land below bit 24
+// in distinct positions, so nothing carries into the result.
+__device__ __forceinline__ uint32_t gather4(uint32_t ones)
+{
+    return (ones * 0x01020408u) >> 24;
+}
+
+// Per-byte "value > 0" for int8 bytes: low seven bits non-zero and sign clear.
+__device__ __forceinline__ uint32_t positive_bytes(uint32_t d)
+{
+    const uint32_t nz = (((d & 0x7F7F7F7Fu) + 0x7F7F7F7Fu) >> 7) & 0x01010101u;
+    return nz & ~(d >> 7);
+}
+
+struct PackGeom {
+    int64_t rows;      // logical rows (matrix rows, pixels, or Cout*R*S)
+    int64_t K;         // values per row
+    int64_t row_stride;// source bytes between rows (within one outer block)
+    int64_t k_stride;  // source bytes between consecutive k
+    int64_t outer_div; // source: row -> (row / outer_div, row % outer_div)
+    int64_t outer_stride; // source bytes per outer block
+    int64_t inner_n;   // destination: row -> (row / inner_n, row % inner_n)
+    int ldw;           // destination words per plane row
+    int bits;
+    int pm1;
+};
+
+// dst word index of (row, plane t, word kw)
+__device__ __forceinline__ size_t dst_index(const PackGeom &g, int64_t row, int t, int kw)
+{
+    const int64_t outer = row / g.inner_n, inner = row - outer * g.inner_n;
+    return (static_cast<size_t>(outer * g.bits + t) * g.inner_n + inner) * g.ldw + kw;
+}
+
+__global__ __launch_bounds__(256) void pack_generic_kernel(const uint8_t *__restrict__ src,
+                                                           uint32_t *__restrict__ dst, PackGeom g)
+{
+    const int64_t idx = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    const int64_t total = g.rows * g.ldw;
+    if (idx >= total) return;
+    const int64_t row = idx / g.ldw;
+    const int kw = static_cast<int>(idx - row * g.ldw);
+    const int64_t ro = row / g.outer_div, ri = row - ro * g.outer_div;
+    const uint8_t *s = src + ro * g.outer_stride + ri * g.row_stride;
+    uint32_t w[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    const int64_t k0 = static_cast<int64_t>(kw) * 32;
+    if (g.k_stride == 1 && k0 + 32 <= g.K && ((reinterpret_cast<uintptr_t>(s + k0) & 15u) == 0)) {
+        const uint4 lo = *reinterpret_cast<const uint4 *>(s + k0);
+        const uint4 hi = *reinterpret_cast<const uint4 *>(s + k0 + 16);
+        const uint32_t d[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            if (g.pm1) {
+                w[0] |= gather4(positive_bytes(d[i])) << (4 * i);
+            } else {
+#pragma unroll
+                for (int t = 0; t < 8; ++t)
+                    if (t < g.bits) w[t] |= gather4((d[i] >> t) & 0x01010101u) << (4 * i);
+            }
+        }
+    } else {
+        for (int b = 0; b < 32; ++b) {
+            const int64_t k = k0 + b;
+            if (k >= g.K) break;
+            const uint8_t v = s[k * g.k_stride];
+            if (g.pm1) {
+                w[0] |= static_cast<uint32_t>(static_cast<int8_t>(v) > 0) << b;
+            } else {
+#pragma unroll
+                for (int t = 0; t < 8; ++t)
+                    if (t < g.bits) w[t] |= ((static_cast<uint32_t>(v) >> t) & 1u) << b;
+            }
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+        if (t < g.bits) dst[dst_index(g, row, t, kw)] = w[t];
+}
+
+__global__ __launch_bounds__(256) void quantize_pack_kernel(const float *__restrict__ src,
+                                                            uint32_t *__restrict__ dst, int64_t rows,
+                                                            int64_t K, int ldw, int bits, float zero,
+                                                            float step)
+{
+    const int64_t idx = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (idx >= rows * ldw) return;
+    const int64_t row = idx / ldw;
+    const int kw = static_cast<int>(idx - row * ldw);
+    const float hi = static_cast<float>((1 << bits) - 1);
+    uint32_t w[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int b = 0; b < 32; ++b) {
+        const int64_t k = static_cast<int64_t>(kw) * 32 + b;
+        if (k >= K) break;
+        // (x - z) / s with one rounding per operation, then floor and clamp
+        const float d = __fsub_rn(src[row * K + k], zero);
+        const float v = __fdiv_rn(d, step);
+        float f = floorf(v);
+        f = (f >= 0.0f) ? f : 0.0f;          // negatives and NaN -> 0
+        f = (f > hi) ? hi : f;
+        const uint32_t code = static_cast<uint32_t>(f);
+#pragma unroll
+        for (int t = 0; t < 8; ++t)
+            if (t < bits) w[t] |= ((code >> t) & 1u) << b;
+    }
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+        if (t < bits) dst[(static_cast<size_t>(row) * bits + t) * ldw + kw] = w[t];
+}
+
+// Input-layer receptive-field packing: word r of an output pixel holds bit
+// (s*C + c) = bit t of image[n][c][ho*stride+r-pad][wo*stride+s-pad].
+__global__ __launch_bounds__(256) void pack_patches_kernel(const uint8_t *__restrict__ img,
+                                                           uint32_t *__restrict__ dst, int64_t npix,
+                                                           int C, int H, int W, int Ho, int Wo, int R, int S,
+                                                           int stride, int pad, int bits, int ldw)
+{
+    const int64_t idx = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (idx >= npix * ldw) return;
+    const int64_t pix = idx / ldw;
+    const int r = static_cast<int>(idx - pix * ldw);
+    const int wo = static_cast<int>(pix % Wo);
+    const int ho = static_cast<int>((pix / Wo) % Ho);
+    const int64_t n = pix / (static_cast<int64_t>(Wo) * Ho);
+    uint32_t w[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    const int h = ho * stride + r - pad;
+    if (r < R && h >= 0 && h < H) {
+        for (int s = 0; s < S; ++s) {
+            const int x = wo * stride + s - pad;
+            if (x < 0 || x >= W) continue;
+            for (int c = 0; c < C; ++c) {
+                const uint32_t v = img[((n * C + c) * H + h) * W + x];
+#pragma unroll
+                for (int t = 0; t < 8; ++t)
+                    if (t < bits) w[t] |= ((v >> t) & 1u) << (s * C + c);
+            }
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+        if (t < bits) dst[(static_cast<size_t>(pix) * bits + t) * ldw + r] = w[t];
+}
+
+__global__ __launch_bounds__(256) void pack_patch_weights_kernel(const uint8_t *__restrict__ wsrc,
+                                                                 uint32_t *__restrict__ dst, int Cout, int Cin,
+                                                                 int R, int S, int bits, int pm1, int ldw)
+{
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx >= Cout * ldw) return;
+    const int co = idx / ldw, r = idx - co * ldw;
+    uint32_t w[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (r < R) {
+        for (int s = 0; s < S; ++s)
+            for (int c = 0; c < Cin; ++c) {
+                const uint8_t v = wsrc[((static_cast<size_t>(co) * Cin + c) * R + r) * S + s];
+                if (pm1) {
+                    w[0] |= static_cast<uint32_t>(static_cast<int8_t>(v) > 0) << (s * Cin + c);
+                } else {
+#pragma unroll
+                    for (int t = 0; t < 8; ++t)
+                        if (t < bits) w[t] |= ((static_cast<uint32_t>(v) >> t) & 1u) << (s * Cin + c);
+                }
+            }
+    }
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+        if (t < bits) dst[(static_cast<size_t>(co) * bits + t) * ldw + r] = w[t];
+}
+
+static int launch_pack(const char *who, const void *src, uint32_t *dst, const PackGeom &g, void *stream)
+{
+    const int64_t total = g.rows * g.ldw;
+    if (total == 0) return APNN_OK;
+    if (total > (int64_t(1) << 38)) return fail(APNN_ERR_INVALID_ARG, "%s: tensor too large", who);
+    const unsigned grid = static_cast<unsigned>(ceil_div(total, 256));
+    hipLaunchKernelGGL(pack_generic_kernel, dim3(grid), dim3(256), 0, as_stream(stream),
+                       static_cast<const uint8_t *>(src), dst, g);
+    return check_launch(who);
+}
+
+}  // namespace apnn
+
+using namespace apnn;
+
+extern "C" int apnn_pack(const void *src_dev, int64_t rows, int64_t K, int bits, apnn_encoding enc,
+                         uint32_t *dst_dev, void *stream)
+{
+    clear_error();
+    if (int rc = check_bits_enc("apnn_pack", "operand", bits, enc)) return rc;
+    if (rows < 0 || K < 0) return fail(APNN_ERR_INVALID_ARG, "apnn_pack: negative size");
+    if (rows == 0 || K == 0) return APNN_OK;
+    if (!src_dev || !dst_dev) return fail(APNN_ERR_INVALID_ARG, "apnn_pack: null pointer");
+    if (!aligned16(dst_dev)) return fail(APNN_ERR_ALIGNMENT, "apnn_pack: dst_dev not 16-byte aligned");
+    PackGeom g{rows, K, K, 1, rows, 0, 1, static_cast<int>(apnn_row_words(K)), bits, enc == APNN_ENC_PM1};
+    if (apnn_row_words(K) > INT32_MAX) return fail(APNN_ERR_INVALID_ARG, "apnn_pack: K too large");
+    return launch_pack("apnn_pack", src_dev, dst_dev, g, stream);
+}
+
+extern "C" int apnn_pack_fmap(const void *src_dev, apnn_layout layout, int64_t N, int64_t H, int64_t W,
+                              int64_t C, int bits, apnn_encoding enc, uint32_t *dst_dev, void *stream)
+{
+    clear_error();
+    if (int rc = check_bits_enc("apnn_pack_fmap", "feature", bits, enc)) return rc;
+    if (N < 0 || H < 0 || W < 0 || C < 0) return fail(APNN_ERR_INVALID_ARG, "apnn_pack_fmap: negative size");
+    if (layout != APNN_LAYOUT_NHWC && layout != APNN_LAYOUT_NCHW)
+        return fail(APNN_ERR_INVALID_ARG, "apnn_pack_fmap: unknown layout %d", static_cast<int>(layout));
+    if (N * H * W * C == 0) return APNN_OK;
+    if (!src_dev || !dst_dev) return fail(APNN_ERR_INVALID_ARG, "apnn_pack_fmap: null pointer");
+    if (!aligned16(dst_dev)) return fail(APNN_ERR_ALIGNMENT, "apnn_pack_fmap: dst_dev not 16-byte aligned");
+    const int64_t HW = H * W;
+    PackGeom g;
+    g.rows = N * HW; g.K = C; g.inner_n = 1; g.ldw = static_cast<int>(ceil_div(C, 32));
+    g.bits = bits; g.pm1 = enc == APNN_ENC_PM1;
+    if (layout == APNN_LAYOUT_NHWC) {
+        g.row_stride = C; g.k_stride = 1; g.outer_div = g.rows; g.outer_stride = 0;
+    } else {
+        g.row_stride = 1; g.k_stride = HW; g.outer_div = HW; g.outer_stride = C * HW;
+    }
+    return launch_pack("apnn_pack_fmap", src_dev, dst_dev, g, stream);
+}
+
+extern "C" int apnn_pack_conv_weights(const void *src_dev, int64_t Cout, int64_t Cin, int R, int S, int bits,
+                                      apnn_encoding enc, uint32_t *dst_dev, void *stream)
+{
+    clear_error();
+    if (int rc = check_bits_enc("apnn_pack_conv_weights", "weight", bits, enc)) return rc;
+    if (Cout < 0 || Cin < 0 || R < 1 || S < 1) return fail(APNN_ERR_INVALID_ARG, "apnn_pack_conv_weights: bad size");
+    if (Cout * Cin == 0) return APNN_OK;
+    if (!src_dev || !dst_dev) return fail(APNN_ERR_INVALID_ARG, "apnn_pack_conv_weights: null pointer");
+    if (!aligned16(dst_dev)) return fail(APNN_ERR_ALIGNMENT, "apnn_pack_conv_weights: dst_dev not 16-byte aligned");
+    const int64_t RS = static_cast<int64_t>(R) * S;
+    PackGeom g;
+    g.rows = Cout * RS; g.K = Cin;           // a "row" is one (cout, r, s) tap, its values are the channels
+    g.row_stride = 1; g.k_stride = RS;       // source Cout x Cin x R x S: tap index is contiguous, channels stride RS
+    g.outer_div = RS; g.outer_stride = Cin * RS;
+    g.inner_n = RS; g.ldw = static_cast<int>(ceil_div(Cin, 32));
+    g.bits = bits; g.pm1 = enc == APNN_ENC_PM1;
+    return launch_pack("apnn_pack_conv_weights", src_dev, dst_dev, g, stream);
+}
+
+extern "C" int apnn_pack_patches(const uint8_t *src_dev, int64_t N, int64_t C, int64_t H, int64_t W, int R, int S,
+                                 int stride, int pad, int bits, uint32_t *dst_dev, void *stream)
+{
+    clear_error();
+    if (int rc = check_bits_enc("apnn_pack_patches", "image", bits, APNN_ENC_UNSIGNED)) return rc;
+    if (N < 0 || C < 1 || H < 1 || W < 1 || R < 1 || S < 1 || stride < 1 || pad < 0)
+        return fail(APNN_ERR_INVALID_ARG, "apnn_pack_patches: bad geometry");
+    if (static_cast<int64_t>(S) * C > 32)
+        return fail(APNN_ERR_UNSUPPORTED, "apnn_pack_patches: S*C = %lld bits do not fit one word", (long long)(S * C));
+    if (H + 2 * pad < R || W + 2 * pad < S) return fail(APNN_ERR_INVALID_ARG, "apnn_pack_patches: kernel larger than padded frame");
+    if (N == 0) return APNN_OK;
+    if (!src_dev || !dst_dev) return fail(APNN_ERR_INVALID_ARG, "apnn_pack_patches: null pointer");
+    if (!aligned16(dst_dev)) return fail(APNN_ERR_ALIGNMENT, "apnn_pack_patches: dst_dev not 16-byte aligned");
+    const int Ho = static_cast<int>((H + 2 * pad - R) / stride + 1), Wo = static_cast<int>((W + 2 * pad - S) / stride + 1);
+    const int ldw = static_cast<int>(apnn_row_words(32 * static_cast<int64_t>(R)));
+    const int64_t npix = N * Ho * Wo;
+    const unsigned grid = static_cast<unsigned>(ceil_div(npix * ldw, 256));
+    hipLaunchKernelGGL(pack_patches_kernel, dim3(grid), dim3(256), 0, as_stream(stream), src_dev, dst_dev, npix,
+                       static_cast<int>(C), static_cast<int>(H), static_cast<int>(W), Ho, Wo, R, S, stride, pad, bits, ldw);
+    return check_launch("apnn_pack_patches");
+}
+
+extern "C" int apnn_pack_patch_weights(const void *src_dev, int64_t Cout, int64_t Cin, int R, int S, int bits,
+                                       apnn_encoding enc, uint32_t *dst_dev, void *stream)
+{
+    clear_error();
+    if (int rc = check_bits_enc("apnn_pack_patch_weights", "weight", bits, enc)) return rc;
+    if (Cout < 0 || Cin < 1 || R < 1 || S < 1) return fail(APNN_ERR_INVALID_ARG, "apnn_pack_patch_weights: bad size");
+    if (static_cast<int64_t>(S) * Cin > 32)
+        return fail(APNN_ERR_UNSUPPORTED, "apnn_pack_patch_weights: S*Cin = %lld bits do not fit one word", (long long)(S * Cin));
+    if (Cout == 0) return APNN_OK;
+    if (!src_dev || !dst_dev) return fail(APNN_ERR_INVALID_ARG, "apnn_pack_patch_weights: null pointer");
+    if (!aligned16(dst_dev)) return fail(APNN_ERR_ALIGNMENT, "apnn_pack_patch_weights: dst_dev not 16-byte aligned");
+    const int ldw = static_cast<int>(apnn_row_words(32 * static_cast<int64_t>(R)));
+    const unsigned grid = static_cast<unsigned>(ceil_div(Cout * ldw, 256));
+    hipLaunchKernelGGL(pack_patch_weights_kernel, dim3(grid), dim3(256), 0, as_stream(stream),
+                       static_cast<const uint8_t *>(src_dev), dst_dev, static_cast<int>(Cout), static_cast<int>(Cin), R, S,
+                       bits, enc == APNN_ENC_PM1 ? 1 : 0, ldw);
+    return check_launch("apnn_pack_patch_weights");
+}
+
+extern "C" int apnn_quantize(const float *src_dev, int64_t rows, int64_t K, float zero, float step, int bits,
+                             uint32_t *dst_dev, void *stream)
+{
+    clear_error();
+    if (int rc = check_bits_enc("apnn_quantize", "output", bits, APNN_ENC_UNSIGNED)) return rc;
+    if (rows < 0 || K < 0) return fail(APNN_ERR_INVALID_ARG, "apnn_quantize: negative size");
+    if (!(step > 0.0f)) return fail(APNN_ERR_INVALID_ARG, "apnn_quantize: step must be > 0");
+    if (rows == 0 || K == 0) return APNN_OK;
+    if (!src_dev || !dst_dev) return fail(APNN_ERR_INVALID_ARG, "apnn_quantize: null pointer");
+    if (!aligned16(dst_dev)) return fail(APNN_ERR_ALIGNMENT, "apnn_quantize: dst_dev not 16-byte aligned");
+    const int ldw = static_cast<int>(apnn_row_words(K));
+    const unsigned grid = static_cast<unsigned>(ceil_div(rows * ldw, 256));
+    hipLaunchKernelGGL(quantize_pack_kernel, dim3(grid), dim3(256), 0, as_stream(stream), src_dev, dst_dev, rows, K,
+                       ldw, bits, zero, step);
+    return check_launch("apnn_quantize");
+}

@@ -1,0 +1,28 @@
+// Instances of the tile kernel with a 8 x 8 register tile per thread.
+#include "tile_launch.h"
+
+namespace apnn {
+
+template <int VW, bool CONV, bool XOR>
+static void go(const TileParams &p, unsigned grid, hipStream_t st)
+{
+    hipLaunchKernelGGL((tile_kernel<8, 8, kTileKC, VW, CONV, XOR>), dim3(grid), dim3(256), 0, st, p);
+}
+
+bool launch_tile8(const TileParams &p, bool conv, int vw, bool use_xor, unsigned grid, hipStream_t st)
+{
+    if (!conv) {
+        if (vw != 4) return false;
+        if (use_xor) go<4, false, true>(p, grid, st); else go<4, false, false>(p, grid, st);
+        return true;
+    }
+    if (use_xor) return false;
+    switch (vw) {
+        case 4: go<4, true, false>(p, grid, st); return true;
+        case 2: go<2, true, false>(p, grid, st); return true;
+        case 1: go<1, true, false>(p, grid, st); return true;
+        default: return false;
+    }
+}
+
+}  // namespace apnn

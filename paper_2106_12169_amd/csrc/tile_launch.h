@@ -1,0 +1,17 @@
+// Launchers of the tile kernel instances; each tile size lives in its own
+// translation unit so the instances compile in parallel.
+#pragma once
+#include "tile_kernel.h"
+
+namespace apnn {
+
+// r = per-thread tile edge (8, 4 or 2); block tile is (16 r) x (16 r).
+// vw = loader vector width in words (matrix mode: 4; conv mode: 4, 2 or 1).
+// Returns false if the combination is not instantiated.
+bool launch_tile8(const TileParams &p, bool conv, int vw, bool use_xor, unsigned grid, hipStream_t st);
+bool launch_tile4(const TileParams &p, bool conv, int vw, bool use_xor, unsigned grid, hipStream_t st);
+bool launch_tile2(const TileParams &p, bool conv, int vw, bool use_xor, unsigned grid, hipStream_t st);
+
+constexpr int kTileKC = 16;   // K words staged per chunk
+
+}  // namespace apnn

@@ -1,0 +1,120 @@
+"""GPU parity of apnn_gemm against the integer oracle: bit-exact int32."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2106_12169_amd import binding as B
+from paper_2106_12169_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+U, P = wl.ENC_UNSIGNED, wl.ENC_PM1
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def gpu_gemm(W, encW, p, X, encX, q):
+    M, K = W.shape
+    N = X.shape[0]
+    Wp, Xp = B.apnn_pack(dev(W), p, encW), B.apnn_pack(dev(X), q, encX)
+    Y = B.apnn_gemm(Wp, Xp, M, N, K, p, q, encW, encX)
+    torch.cuda.synchronize()
+    return Y.cpu().numpy()
+
+
+@pytest.fixture(params=["auto", "8", "4", "2"])
+def tile(request, monkeypatch):
+    if request.param != "auto":
+        monkeypatch.setenv("APNN_TILE", request.param)
+    else:
+        monkeypatch.delenv("APNN_TILE", raising=False)
+    return request.param
+
+
+CASES = [
+    # encW, p, encX, q, M, N, K
+    (P, 1, U, 2, 128, 128, 128),          # benchmark configuration 0
+    (U, 1, U, 1, 130, 70, 200),
+    (P, 1, U, 2, 257, 131, 1000),         # several tiles, ragged M/N/K tails
+    (U, 2, U, 2, 96, 160, 513),
+    (U, 1, U, 4, 64, 64, 2048),
+    (U, 3, U, 5, 50, 90, 777),
+    (U, 2, U, 8, 33, 47, 300),
+    (U, 8, U, 8, 20, 20, 4000),
+    (P, 1, P, 1, 140, 150, 999),          # Case II (XOR), K not a multiple of 32
+    (U, 4, P, 1, 75, 129, 640),           # mirrored Case III
+    (P, 1, U, 8, 129, 65, 96),
+    (U, 1, U, 1, 1, 1, 1),
+    (P, 1, U, 2, 3, 1000, 64),            # FC-like thin shapes
+]
+
+
+@pytest.mark.parametrize("encW,p,encX,q,M,N,K", CASES)
+def test_gemm_matches_oracle(tile, encW, p, encX, q, M, N, K):
+    W = wl.operand(11 * M + K, M, K, p, encW)
+    X = wl.operand(13 * N + K, N, K, q, encX)
+    got = gpu_gemm(W, encW, p, X, encX, q)
+    assert np.array_equal(got, oracle.gemm(W, encW, p, X, encX, q))
+
+
+def test_gemm_extremes_and_empty():
+    K = 700
+    W = np.full((40, K), 255, np.uint8)
+    assert (gpu_gemm(W, U, 8, W, U, 8) == K * 255 * 255).all()        # largest accumulators
+    Z = np.zeros((40, K), np.uint8)
+    assert (gpu_gemm(W, U, 8, Z, U, 8) == 0).all()
+    ones = np.ones((40, K), np.int8)
+    assert (gpu_gemm(ones, P, 1, -ones, P, 1) == -K).all()
+    # K = 0 writes zeros; M = 0 / N = 0 write nothing
+    Y = torch.full((4, 5), 7, dtype=torch.int32, device="cuda")
+    e = torch.empty(1, dtype=torch.int32, device="cuda")
+    B.apnn_gemm(e, e, 4, 5, 0, 1, 2, P, U, out=Y)
+    assert (Y.cpu().numpy() == 0).all()
+    Y.fill_(7)
+    B.apnn_gemm(e, e, 0, 5, 64, 1, 2, P, U, out=Y)
+    assert (Y.cpu().numpy() == 7).all()
+
+
+def test_gemm_is_deterministic():
+    wk = wl.gemm_w1a2(512, 0)
+    a = gpu_gemm(wk.weights(), P, 1, wk.activations(), U, 2)
+    b = gpu_gemm(wk.weights(), P, 1, wk.activations(), U, 2)
+    assert np.array_equal(a, b)
+
+
+@pytest.mark.parametrize("w,a", wl.SWEEP_BITS)
+def test_sweep_reduced_size(w, a):
+    wk = wl.sweep_workload(w, a, 384)
+    W, X = wk.weights(), wk.activations()
+    assert np.array_equal(gpu_gemm(W, U, w, X, U, a), oracle.gemm(W, U, w, X, U, a))
+
+
+def test_config1_full_size_sampled_rows_and_properties():
+    """4096^3 in the launch configuration the benchmark times: 48 sampled rows
+    element by element against the oracle, plus size-independent properties."""
+    wk = wl.CONFIG1
+    W, X = wk.weights(), wk.activations()
+    Y = gpu_gemm(W, wk.encW, wk.p, X, wk.encX, wk.q)
+    rows = np.unique(np.concatenate([[0, 1, 127, 128, 4095], (wl.raw_u64(5, 0, 43) % np.uint64(4096)).astype(int)]))
+    want = oracle.gemm(W[rows], wk.encW, wk.p, X, wk.encX, wk.q)
+    assert np.array_equal(Y[rows], want)
+    # parity of every entry: sum of K odd/even terms -> Y = rowsum(X) (mod 2)
+    assert np.array_equal(Y & 1, np.broadcast_to(X.astype(np.int64).sum(1) & 1, Y.shape))
+    # column sums: sum_m Y[m][n] = sum_k (sum_m W[m][k]) X[n][k]
+    colw = W.astype(np.int64).sum(0)
+    assert np.array_equal(Y.astype(np.int64).sum(0), X.astype(np.int64) @ colw)
+
+
+@pytest.mark.parametrize("w,a", wl.SWEEP_BITS)
+def test_config2_full_size_sampled(w, a):
+    wk = wl.sweep_workload(w, a)
+    W, X = wk.weights(), wk.activations()
+    Y = gpu_gemm(W, U, w, X, U, a)
+    rows = np.unique(np.concatenate([[0, 2047], (wl.raw_u64(6, 0, 14) % np.uint64(2048)).astype(int)]))
+    assert np.array_equal(Y[rows], oracle.gemm(W[rows], U, w, X, U, a))
+    colw = W.astype(np.int64).sum(0)
+    assert np.array_equal(Y.astype(np.int64).sum(0), X.astype(np.int64) @ colw)
