@@ -1,0 +1,179 @@
+"""GPU parity of apnn_conv2d / apnn_layer / pooling against the oracle:
+int32 accumulators and requantised codes bit-exact, fp32 pre-floor values
+within 1e-5 relative (they are in fact the same single fma)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2106_12169_amd import binding as B
+from paper_2106_12169_amd import workloads as wl
+from tests import helpers as hp
+
+pytestmark = pytest.mark.gpu
+U, P = wl.ENC_UNSIGNED, wl.ENC_PM1
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+@pytest.fixture(params=["auto", "8", "4", "2"])
+def tile(request, monkeypatch):
+    if request.param != "auto":
+        monkeypatch.setenv("APNN_TILE", request.param)
+    else:
+        monkeypatch.delenv("APNN_TILE", raising=False)
+    return request.param
+
+
+def run_conv(Wv, encW, p, Xv, q, stride, pad):
+    Cout, Cin, R, S = Wv.shape
+    N, _, H, Wd = Xv.shape
+    d = B.Conv(N, H, Wd, Cin, Cout, R, S, stride, pad, p, q, encW, U)
+    Wp = B.apnn_pack_conv_weights(dev(Wv), p, encW)
+    Xp = B.apnn_pack_fmap(dev(Xv), B.LAYOUT_NCHW, q, U)
+    Y = B.apnn_conv2d(d, Wp, Xp)
+    torch.cuda.synchronize()
+    return Y.cpu().numpy().transpose(0, 3, 1, 2), d, Wp, Xp     # -> N x Cout x Ho x Wo
+
+
+CONVS = [
+    # Cin, Cout, H, W, R, stride, pad, encW, p, q, batch
+    (128, 128, 28, 28, 3, 1, 1, P, 1, 2, 2),     # configuration-3 family (vector width 4)
+    (64, 64, 14, 14, 3, 1, 1, P, 1, 2, 3),       # 2 channel words
+    (64, 128, 15, 13, 3, 2, 1, P, 1, 2, 2),      # stride 2, odd frame
+    (64, 128, 14, 14, 1, 2, 0, P, 1, 2, 2),      # 1x1 stride-2 shortcut
+    (32, 32, 9, 9, 3, 1, 1, P, 1, 2, 1),         # 1 channel word
+    (96, 64, 8, 8, 3, 1, 1, U, 2, 3, 1),         # 3 channel words, unsigned weights
+    (256, 96, 7, 7, 3, 1, 1, P, 1, 2, 2),        # Cout not a multiple of the tile
+    (128, 64, 6, 6, 5, 1, 2, U, 1, 1, 1),        # 5x5
+    (512, 512, 7, 7, 3, 1, 1, P, 1, 2, 1),       # last-stage shape
+]
+
+
+@pytest.mark.parametrize("Cin,Cout,H,Wd,R,stride,pad,encW,p,q,BS", CONVS)
+def test_conv2d_matches_oracle(tile, Cin, Cout, H, Wd, R, stride, pad, encW, p, q, BS):
+    Wv = wl.operand(31 + Cin + Cout, Cout, Cin * R * R, p, encW).reshape(Cout, Cin, R, R)
+    Xv = wl.uniform_codes(32 + H, (BS, Cin, H, Wd), q)
+    got, *_ = run_conv(Wv, encW, p, Xv, q, stride, pad)
+    assert np.array_equal(got, oracle.conv2d(Wv, encW, p, Xv, U, q, stride, pad))
+
+
+def test_conv_pm1_pm1_is_refused():
+    d = B.Conv(1, 8, 8, 32, 32, 3, 3, 1, 1, 1, 1, P, P)
+    e = torch.zeros(4096, dtype=torch.int32, device="cuda")
+    with pytest.raises(B.ApnnError) as ei:
+        B.apnn_conv2d(d, e, e)
+    assert ei.value.status == 2
+
+
+def _layer_case(BS, Cin, Cout, H, R, stride, pad, q, q_out, with_res, seed):
+    Wv = wl.fair_signs(seed, (Cout, Cin, R, R))
+    Xv = wl.uniform_codes(seed + 1, (BS, Cin, H, H), q)
+    K = Cin * R * R
+    scale = (wl.normals(seed + 2, (Cout,), 1.0, 0.2) / np.sqrt(K * 3.5)).astype(np.float32)
+    bias = wl.normals(seed + 3, (Cout,), 0.5 * (1 << q_out), 0.3)
+    d = B.Conv(BS, H, H, Cin, Cout, R, R, stride, pad, 1, q, P, U)
+    res = wl.uniform_codes(seed + 4, (BS, Cout, d.Ho, d.Wo), 2) if with_res else None
+    return Wv, Xv, scale, bias, res, d
+
+
+@pytest.mark.parametrize("BS,Cin,Cout,H,R,stride,pad,q,q_out,with_res", [
+    (2, 128, 128, 14, 3, 1, 1, 2, 2, False),
+    (2, 128, 128, 14, 3, 1, 1, 2, 2, True),
+    (1, 64, 64, 12, 3, 1, 1, 2, 2, True),
+    (2, 64, 96, 9, 3, 2, 1, 2, 3, False),
+    (1, 256, 32, 7, 3, 1, 1, 2, 1, True),
+    (1, 64, 160, 8, 1, 1, 0, 2, 8, False),
+])
+def test_fused_layer_matches_oracle(tile, BS, Cin, Cout, H, R, stride, pad, q, q_out, with_res):
+    Wv, Xv, scale, bias, res, d = _layer_case(BS, Cin, Cout, H, R, stride, pad, q, q_out, with_res, 50 + Cin + q_out)
+    Wp = B.apnn_pack_conv_weights(dev(Wv), 1, P)
+    Xp = B.apnn_pack_fmap(dev(Xv), B.LAYOUT_NCHW, q, U)
+    resp = B.apnn_pack_fmap(dev(res), B.LAYOUT_NCHW, 2, U) if with_res else None
+    acc = torch.empty((d.N, d.Ho, d.Wo, Cout), dtype=torch.int32, device="cuda")
+    tf = torch.empty((d.N, d.Ho, d.Wo, Cout), dtype=torch.float32, device="cuda")
+    out = B.apnn_layer(d, Wp, Xp, q_out=q_out, scale=dev(scale), bias=dev(bias), residual=resp, q_res=2,
+                       res_scale=0.5, acc_out=acc, float_out=tf)
+    torch.cuda.synchronize()
+    want_acc = oracle.conv2d(Wv, P, 1, Xv, U, q, stride, pad)
+    want_codes, want_t = oracle.epilogue(want_acc, scale, bias, q_out, res=res, res_scale=0.5, want_t=True)
+    assert np.array_equal(acc.cpu().numpy().transpose(0, 3, 1, 2), want_acc)
+    got_t = tf.cpu().numpy().transpose(0, 3, 1, 2)
+    assert np.allclose(got_t, want_t, rtol=1e-5, atol=0) and np.array_equal(got_t, want_t)
+    codes, pad_bits = hp.unpack_fmap(hp.words_u32(out), d.N, d.Ho, d.Wo, Cout, q_out)
+    assert np.array_equal(codes, want_codes) and pad_bits == 0
+    assert len(np.unique(want_codes)) == (1 << q_out) if q_out <= 3 else True
+
+
+def test_config3_full_layer():
+    """Configuration 3 as given (N(0,1) scale, N(0,0.1) bias) and a spread variant
+    that exercises all four codes."""
+    c = wl.CONFIG3
+    Wv, Xv = c.weights_oihw(), c.features_nchw()
+    d = B.Conv(c.BS, c.H, c.W, c.Cin, c.Cout, c.R, c.S, c.stride, c.pad, c.p, c.q, c.encW, c.encX)
+    Wp = B.apnn_pack_conv_weights(dev(Wv), c.p, c.encW)
+    Xp = B.apnn_pack_fmap(dev(Xv), B.LAYOUT_NCHW, c.q, c.encX)
+    want_acc = oracle.conv2d(Wv, c.encW, c.p, Xv, c.encX, c.q, c.stride, c.pad)
+    for scale, bias in ((c.scale(), c.bias()), ((c.scale() / 64).astype(np.float32), (c.bias() + 1.5).astype(np.float32))):
+        acc = torch.empty((d.N, d.Ho, d.Wo, c.Cout), dtype=torch.int32, device="cuda")
+        tf = torch.empty((d.N, d.Ho, d.Wo, c.Cout), dtype=torch.float32, device="cuda")
+        out = B.apnn_layer(d, Wp, Xp, q_out=c.q_out, scale=dev(scale), bias=dev(bias), acc_out=acc, float_out=tf)
+        torch.cuda.synchronize()
+        want_codes, want_t = oracle.epilogue(want_acc, scale, bias, c.q_out, want_t=True)
+        assert np.array_equal(acc.cpu().numpy().transpose(0, 3, 1, 2), want_acc)
+        got_t = tf.cpu().numpy().transpose(0, 3, 1, 2)
+        rel = np.abs(got_t - want_t) / np.maximum(np.abs(want_t), 1e-30)
+        assert rel.max() <= 1e-5
+        codes, _ = hp.unpack_fmap(hp.words_u32(out), d.N, d.Ho, d.Wo, c.Cout, c.q_out)
+        assert np.array_equal(codes, want_codes)
+    assert len(np.unique(want_codes)) == 4
+
+
+def test_gemm_layer_fc_shape():
+    """Fully connected layer: 8-bit activations x +-1 weights, int32 logits, ragged Cout."""
+    BS, K, Cout = 8, 512, 1000
+    Xv = wl.uniform_codes(1, (BS, K), 8)
+    Wv = wl.fair_signs(2, (Cout, K))
+    d = B.Conv(BS, 1, 1, K, Cout, 1, 1, 1, 0, 1, 8, P, U)
+    logits = torch.empty((BS, Cout), dtype=torch.int32, device="cuda")
+    B.apnn_layer(d, B.apnn_pack(dev(Wv), 1, P), B.apnn_pack(dev(Xv), 8, U), is_gemm=True, acc_out=logits)
+    torch.cuda.synchronize()
+    assert np.array_equal(logits.cpu().numpy(), oracle.gemm(Xv, U, 8, Wv, P, 1))
+
+
+@pytest.mark.parametrize("k,stride,pad,bits,C,H", [(3, 2, 1, 2, 64, 13), (2, 2, 0, 2, 32, 8), (3, 1, 1, 3, 96, 6)])
+def test_maxpool(k, stride, pad, bits, C, H):
+    Xv = wl.uniform_codes(3, (2, C, H, H), bits)
+    Xp = B.apnn_pack_fmap(dev(Xv), B.LAYOUT_NCHW, bits, U)
+    out = B.apnn_maxpool(Xp, 2, H, H, C, bits, k, stride, pad)
+    want = oracle.maxpool(Xv, k, stride, pad)
+    codes, _ = hp.unpack_fmap(hp.words_u32(out), 2, want.shape[2], want.shape[3], C, bits)
+    assert np.array_equal(codes, want)
+
+
+@pytest.mark.parametrize("C,H", [(512, 7), (64, 3), (96, 5)])
+def test_sumpool(C, H):
+    Xv = wl.uniform_codes(4, (3, C, H, H), 2)
+    Xp = B.apnn_pack_fmap(dev(Xv), B.LAYOUT_NCHW, 2, U)
+    out = B.apnn_sumpool(Xp, 3, H, H, C, 2, 8)
+    codes, pad = hp.unpack_matrix(hp.words_u32(out), 3, C, 8)
+    assert np.array_equal(codes, oracle.sumpool(Xv)) and pad == 0
+
+
+def test_first_layer_patches_equal_convolution():
+    """Input layer: 8-bit image planes x +-1 weights through the receptive-field
+    packer and the matrix kernel must equal the 7x7 stride-2 convolution."""
+    BS, HW, Cout = 2, 38, 64
+    img = wl.image_batch(5, BS, HW)
+    Wv = wl.fair_signs(6, (Cout, 3, 7, 7))
+    Xp = B.apnn_pack_patches(dev(img), 7, 7, 2, 3, 8)
+    Wp = B.apnn_pack_patch_weights(dev(Wv), 1, P)
+    Ho = (HW + 6 - 7) // 2 + 1
+    d = B.Conv(BS * Ho * Ho, 1, 1, 32 * 7, Cout, 1, 1, 1, 0, 1, 8, P, U)
+    acc = torch.empty((BS * Ho * Ho, Cout), dtype=torch.int32, device="cuda")
+    B.apnn_layer(d, Wp, Xp, is_gemm=True, acc_out=acc)
+    torch.cuda.synchronize()
+    want = oracle.conv2d(Wv, P, 1, img, U, 8, 2, 3)
+    assert np.array_equal(acc.cpu().numpy().reshape(BS, Ho, Ho, Cout).transpose(0, 3, 1, 2), want)

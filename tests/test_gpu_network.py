@@ -1,0 +1,64 @@
+"""GPU parity of the chained residual network: every node's packed codes and
+the int32 logits bit-exact against the chained oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import network as onet
+from paper_2106_12169_amd import workloads as wl
+from paper_2106_12169_amd.network import PackedNet
+from tests import helpers as hp
+
+pytestmark = pytest.mark.gpu
+
+
+def _check_all_nodes(layers, net, want, batch):
+    for L in layers:
+        got = hp.words_u32(net.buf[L.name])
+        if L.kind == "fc":
+            assert np.array_equal(net.buf[L.name].cpu().numpy(), want[L.name]), L.name
+        elif L.kind == "sumpool":
+            codes, pad = hp.unpack_matrix(got, batch, L.Cout, L.q_out)
+            assert np.array_equal(codes, want[L.name]) and pad == 0, L.name
+        else:
+            codes, pad = hp.unpack_fmap(got, batch, L.Ho, L.Wo, L.Cout, L.q_out)
+            assert np.array_equal(codes, want[L.name]) and pad == 0, L.name
+
+
+def test_small_network_every_node():
+    layers = wl.resnet18_layers(image_hw=64, num_classes=100, widths=(32, 64, 96, 128))
+    params = wl.network_params(layers, seed=1)
+    img = wl.image_batch(3, 2, 64)
+    net = PackedNet(layers, params, 2)
+    net.forward(torch.from_numpy(img).cuda())
+    torch.cuda.synchronize()
+    _check_all_nodes(layers, net, onet.run(layers, params, img), 2)
+
+
+def test_resnet18_shape_batch8_logits_and_graph_replay():
+    """Configuration 4 at full size, eagerly and as a HIP-graph replay."""
+    layers = wl.resnet18_layers()
+    params = wl.network_params(layers)
+    img = wl.image_batch(2004, 8, 224)
+    net = PackedNet(layers, params, 8)
+    d_img = torch.from_numpy(img).cuda()
+    logits = net.forward(d_img).clone()
+    torch.cuda.synchronize()
+    want = onet.run(layers, params, img)
+    _check_all_nodes(layers, net, want, 8)
+    assert np.array_equal(logits.cpu().numpy(), want["fc"])
+    # graph capture of the same launches; replays must reproduce the eager result
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        net.forward(d_img)
+    torch.cuda.current_stream().wait_stream(s)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        net.forward(d_img)
+    for _ in range(3):
+        net.buf["fc"].zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(net.buf["fc"].cpu().numpy(), want["fc"])
