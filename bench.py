@@ -1,0 +1,204 @@
+#!/usr/bin/env python3
+"""Benchmark of the arbitrary-precision bit-plane hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-extra] [--no-cpu]
+
+A step is one pass of the hot path on the headline workload (benchmark
+configuration 1: w1a2 GEMM, M = N = K = 4096, +-1 weights, unsigned 2-bit
+activations): bit-decompose and pack the activations, then the bit-plane GEMM
+(plane-pair AND + popcount, shift-add, Case III recovery) to int32.  Weights
+are packed once before timing (they are quantised at initialisation, Sec. 5.1).
+All inputs are resident in HBM when the timed region starts.
+
+Prints ONE JSON line: effective TOPS (2 M N K / time), the roofline of the
+dominant kernel (VALU bitwise+popcount issue rate) measured with events around
+each of its launches inside the timed region, and the CPU oracle timed on a
+bounded row sample.  The other benchmark configurations are reported under
+"extra" (device time per launch via HIP-graph replay).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+VALU_PEAK_LANE_OPS = 256 * 64 * 2.4e9      # 256 CUs x 64 lanes/clk x 2.4 GHz (32-bit integer vector ops)
+HBM_PEAK = 8.0e12
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def graph_time(fn, reps=20, replays=5):
+    """Device seconds per call of fn, from replays of a HIP graph holding `reps` calls."""
+    import torch
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        fn()
+    torch.cuda.current_stream().wait_stream(s)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for _ in range(reps):
+            fn()
+    g.replay()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(replays):
+        g.replay()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) * 1e-3 / (reps * replays)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)      # the paper averages 200 executions (Sec. 6)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-extra", action="store_true")
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also launch one 256 MiB apnn_probe_copy (reference for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
+
+    import numpy as np
+    import torch
+    from paper_2106_12169_amd import binding as B
+    from paper_2106_12169_amd import workloads as wl
+
+    B.lib()                                       # fails loudly if the HIP library is missing
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+    wk = wl.CONFIG1
+    Wv, Xv = wk.weights(), wk.activations()
+    Wd, Xd = dev(Wv), dev(Xv)
+    Wp = B.apnn_pack(Wd, wk.p, wk.encW)           # init-time weight packing
+    Xp = torch.empty(B.apnn_packed_words(wk.N, wk.K, wk.q), dtype=torch.int32, device="cuda")
+    Y = torch.empty((wk.M, wk.N), dtype=torch.int32, device="cuda")
+
+    def step(ev=None):
+        B.apnn_pack(Xd, wk.q, wk.encX, out=Xp)
+        if ev is not None:
+            ev[0].record()
+        B.apnn_gemm(Wp, Xp, wk.M, wk.N, wk.K, wk.p, wk.q, wk.encW, wk.encX, out=Y)
+        if ev is not None:
+            ev[1].record()
+
+    if args.copy_probe:
+        src = torch.zeros(1 << 28, dtype=torch.uint8, device="cuda")
+        B.apnn_probe_copy(src, torch.empty_like(src))
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(evs[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    sec_per_step = (t1 - t0) / args.steps
+    kern = np.array([a.elapsed_time(b) for a, b in evs]) * 1e-3
+    gemm_s = float(kern.mean())
+    lane_ops = 2.0 * wk.M * wk.N * wk.K * wk.p * wk.q / 32.0     # AND + popcount-accumulate per 32 bit-products
+    achieved = lane_ops / gemm_s
+
+    # cheap self-check on the timed output (full parity lives in tests/)
+    colsum = Y.sum(dim=0, dtype=torch.int64).cpu().numpy()
+    want = Xv.astype(np.int64) @ Wv.astype(np.int64).sum(0)
+    assert np.array_equal(colsum, want), "timed output failed its column-sum check"
+
+    out = {
+        "metric": "effective TOPS, w1a2 4096^3 bit-GEMM (2*M*N*K / time)",
+        "value": round(wk.effective_ops / sec_per_step / 1e12, 2),
+        "unit": "TOPS",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(sec_per_step * 1e3, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u32 bit planes -> int32", "data": "synthetic",
+        "config": {"workload": "config1: w1a2 GEMM M=N=K=4096, +-1 weights x unsigned 2-bit activations, int32 out",
+                   "step": "apnn_pack(activations) + apnn_gemm", "seeds": [wk.seedW, wk.seedX]},
+        "roofline": {
+            "bound": "alu", "kernel": "tile_kernel<8,8,16,4,gemm,AND>",
+            "achieved": round(achieved / 1e12, 3), "peak": round(VALU_PEAK_LANE_OPS / 1e12, 3),
+            "unit": "T lane-op/s (32-bit VALU: v_and + v_bcnt per 32 bit-products)",
+            "frac": round(achieved / VALU_PEAK_LANE_OPS, 4),
+            "kernel_us": round(gemm_s * 1e6, 2),
+            "traffic": None,
+        },
+    }
+
+    if not args.no_cpu:
+        import oracle
+        rows = 32
+        t = time.perf_counter()
+        oracle.gemm_rows(Wv, wk.encW, wk.p, Xv, wk.encX, wk.q, 0, rows)
+        dt = time.perf_counter() - t
+        rows = int(min(wk.M, max(rows, rows * 15.0 / max(dt, 1e-3))))      # aim at ~15 s of CPU work
+        rows -= rows % oracle.threads() or 0
+        t = time.perf_counter()
+        ref = oracle.gemm_rows(Wv, wk.encW, wk.p, Xv, wk.encX, wk.q, 0, rows)
+        dt = time.perf_counter() - t
+        assert np.array_equal(Y[:rows].cpu().numpy(), ref), "GPU result differs from the oracle on the sampled rows"
+        out["cpu_baseline"] = {"value": round(2.0 * rows * wk.N * wk.K / dt / 1e12, 5), "unit": "TOPS",
+                               "cores": oracle.threads(), "kind": "oracle",
+                               "sample": f"rows 0..{rows - 1} of the same 4096^3 product ({dt:.1f} s), also compared bit-exactly"}
+
+    if not args.no_extra:
+        out["extra"] = extra_configs(B, wl, dev, graph_time)
+
+    print(json.dumps(out), flush=True)
+
+
+def extra_configs(B, wl, dev, graph_time):
+    """Device time of the other benchmark configurations (HIP-graph replays)."""
+    import torch
+    from paper_2106_12169_amd.network import PackedNet
+    ex = {}
+
+    def gemm_case(wk):
+        Wp = B.apnn_pack(dev(wk.weights()), wk.p, wk.encW)
+        Xp = B.apnn_pack(dev(wk.activations()), wk.q, wk.encX)
+        Y = torch.empty((wk.M, wk.N), dtype=torch.int32, device="cuda")
+        t = graph_time(lambda: B.apnn_gemm(Wp, Xp, wk.M, wk.N, wk.K, wk.p, wk.q, wk.encW, wk.encX, out=Y))
+        lane = 2.0 * wk.M * wk.N * wk.K * wk.p * wk.q / 32.0
+        return {"us": round(t * 1e6, 2), "eff_tops": round(wk.effective_ops / t / 1e12, 2),
+                "valu_frac": round(lane / t / VALU_PEAK_LANE_OPS, 4)}
+
+    ex["config0_gemm_w1a2_128"] = gemm_case(wl.CONFIG0)
+    ex["config2_sweep_2048"] = {f"w{wk.p}a{wk.q}": gemm_case(wk) for wk in wl.CONFIG2}
+
+    c = wl.CONFIG3
+    d = B.Conv(c.BS, c.H, c.W, c.Cin, c.Cout, c.R, c.S, c.stride, c.pad, c.p, c.q, c.encW, c.encX)
+    Wp = B.apnn_pack_conv_weights(dev(c.weights_oihw()), c.p, c.encW)
+    Xp = B.apnn_pack_fmap(dev(c.features_nchw()), B.LAYOUT_NCHW, c.q, c.encX)
+    sc, bi = dev(c.scale()), dev(c.bias())
+    outp = torch.empty(B.apnn_fmap_words(d.N * d.Ho * d.Wo, c.Cout, c.q_out), dtype=torch.int32, device="cuda")
+    t = graph_time(lambda: B.apnn_layer(d, Wp, Xp, q_out=c.q_out, scale=sc, bias=bi, out=outp))
+    lane = c.effective_ops * c.p * c.q / 32.0
+    ex["config3_conv_layer"] = {"us": round(t * 1e6, 2), "eff_tops": round(c.effective_ops / t / 1e12, 2),
+                                "valu_frac": round(lane / t / VALU_PEAK_LANE_OPS, 4),
+                                "what": "fused conv + scale/bias + requantise + repack, packed in/out"}
+
+    layers = wl.resnet18_layers()
+    net = PackedNet(layers, wl.network_params(layers), 8)
+    img = dev(wl.image_batch(2004, 8, 224))
+    t = graph_time(lambda: net.forward(img), reps=1, replays=50)
+    ex["config4_resnet18_w1a2_batch8"] = {"ms": round(t * 1e3, 4), "launches": len(layers) + 1,
+                                          "what": "HIP-graph replay, 8-bit image in, int32 logits out"}
+    return ex
+
+
+if __name__ == "__main__":
+    main()
