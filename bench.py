@@ -130,7 +130,7 @@ def main():
         "config": {"workload": "config1: w1a2 GEMM M=N=K=4096, +-1 weights x unsigned 2-bit activations, int32 out",
                    "step": "apnn_pack(activations) + apnn_gemm", "seeds": [wk.seedW, wk.seedX]},
         "roofline": {
-            "bound": "alu", "kernel": "tile_kernel<8,8,16,4,gemm,AND>",
+            "bound": "alu", "kernel": "tile_kernel<4,4,16,4,4,false,false> (64x64 tile, AND)",
             "achieved": round(achieved / 1e12, 3), "peak": round(VALU_PEAK_LANE_OPS / 1e12, 3),
             "unit": "T lane-op/s (32-bit VALU: v_and + v_bcnt per 32 bit-products)",
             "frac": round(achieved / VALU_PEAK_LANE_OPS, 4),

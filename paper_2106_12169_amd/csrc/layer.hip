@@ -7,22 +7,21 @@
 
 namespace apnn {
 
-// Tile choice in the spirit of Sec. 4.3: prefer the largest block tile (highest
-// compute intensity 2 bm bn / (bm + bn)) whose grid still gives every one of the
-// 256 compute units at least ~2 blocks; fall back to smaller tiles to recover
-// thread-level parallelism on small problems.
+// Tile choice in the spirit of Sec. 4.3 (thread-level parallelism first, then
+// compute intensity), with the constants re-fitted to 256 compute units.
+// APNN_TILE=8|4|2 overrides the choice (experiments, tests).
 static int pick_tile(int64_t M, int64_t N)
 {
     if (const char *e = std::getenv("APNN_TILE")) {
         const int r = std::atoi(e);
         if (r == 8 || r == 4 || r == 2) return r;
     }
-    auto blocks = [&](int r) { return ceil_div(M, 16 * r) * ceil_div(N, 16 * r); };
-    if (blocks(8) >= 512) return 8;
-    if (blocks(4) >= 384) return 4;
-    if (blocks(8) >= 256) return 8;
-    if (blocks(4) >= 192) return 4;
-    return 2;
+    // Measured on MI355X: the 64 x 64 tile (4 waves per SIMD) matches or beats the
+    // 128 x 128 tile (2 waves per SIMD) from 1024^2 outputs up, because the extra
+    // resident waves cover block start-up and drain; below one block per compute
+    // unit the 32 x 32 tile recovers thread-level parallelism.
+    const int64_t tiles4 = ceil_div(M, 64) * ceil_div(N, 64);
+    return tiles4 >= 256 ? 4 : 2;
 }
 
 struct Problem {
@@ -46,10 +45,24 @@ static int run_tile(const Problem &pr, TileParams &p, int vw, void *stream)
     } else if (b_pm) {
         p.alpha = 2; p.uA = -1;
     }
-    const int r = pick_tile(pr.M, pr.N);
+    int r = pick_tile(pr.M, pr.N);
+    if (pr.conv && vw == 2 && r == 8) r = 4;     // instantiated register tiles per loader width
+    if (pr.conv && vw == 1) r = 2;
     const int64_t tiles = ceil_div(pr.M, 16 * r) * ceil_div(pr.N, 16 * r);
     if (tiles > 0x7FFFFFFF) return fail(APNN_ERR_INVALID_ARG, "%s: problem too large for one launch", pr.who);
-    p.xcd_remap = (tiles % 8 == 0 && tiles >= 16) ? 1 : 0;
+    // XCD-aware tile order: among the factorizations of 8 that divide the tile
+    // grid, take the one with the smallest per-XCD operand footprint.
+    p.xm = p.xn = 0;
+    {
+        const int64_t tM = ceil_div(pr.M, 16 * r), tN = ceil_div(pr.N, 16 * r);
+        double best = 0.0;
+        for (int xm = 1; xm <= 8; xm *= 2) {
+            const int xn = 8 / xm;
+            if (tM % xm != 0 || tN % xn != 0) continue;
+            const double foot = static_cast<double>(tM / xm) * pr.PA + static_cast<double>(tN / xn) * pr.PB;
+            if (p.xm == 0 || foot < best) { best = foot; p.xm = xm; p.xn = xn; }
+        }
+    }
     p.nk = static_cast<int>(ceil_div(p.Kw, kTileKC));
     const unsigned grid = static_cast<unsigned>(tiles);
     bool ok = false;

@@ -6,7 +6,7 @@ namespace apnn {
 template <int VW, bool CONV, bool XOR>
 static void go(const TileParams &p, unsigned grid, hipStream_t st)
 {
-    hipLaunchKernelGGL((tile_kernel<2, 2, kTileKC, VW, CONV, XOR>), dim3(grid), dim3(256), 0, st, p);
+    hipLaunchKernelGGL((tile_kernel<2, 2, kTileKC, VW, kTileLV, CONV, XOR>), dim3(grid), dim3(256), 0, st, p);
 }
 
 bool launch_tile2(const TileParams &p, bool conv, int vw, bool use_xor, unsigned grid, hipStream_t st)

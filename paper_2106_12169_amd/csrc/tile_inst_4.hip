@@ -6,7 +6,7 @@ namespace apnn {
 template <int VW, bool CONV, bool XOR>
 static void go(const TileParams &p, unsigned grid, hipStream_t st)
 {
-    hipLaunchKernelGGL((tile_kernel<4, 4, kTileKC, VW, CONV, XOR>), dim3(grid), dim3(256), 0, st, p);
+    hipLaunchKernelGGL((tile_kernel<4, 4, kTileKC, VW, kTileLV, CONV, XOR>), dim3(grid), dim3(256), 0, st, p);
 }
 
 bool launch_tile4(const TileParams &p, bool conv, int vw, bool use_xor, unsigned grid, hipStream_t st)
@@ -20,7 +20,6 @@ bool launch_tile4(const TileParams &p, bool conv, int vw, bool use_xor, unsigned
     switch (vw) {
         case 4: go<4, true, false>(p, grid, st); return true;
         case 2: go<2, true, false>(p, grid, st); return true;
-        case 1: go<1, true, false>(p, grid, st); return true;
         default: return false;
     }
 }

@@ -6,7 +6,7 @@ namespace apnn {
 template <int VW, bool CONV, bool XOR>
 static void go(const TileParams &p, unsigned grid, hipStream_t st)
 {
-    hipLaunchKernelGGL((tile_kernel<8, 8, kTileKC, VW, CONV, XOR>), dim3(grid), dim3(256), 0, st, p);
+    hipLaunchKernelGGL((tile_kernel<8, 8, kTileKC, VW, kTileLV, CONV, XOR>), dim3(grid), dim3(256), 0, st, p);
 }
 
 bool launch_tile8(const TileParams &p, bool conv, int vw, bool use_xor, unsigned grid, hipStream_t st)
@@ -17,12 +17,10 @@ bool launch_tile8(const TileParams &p, bool conv, int vw, bool use_xor, unsigned
         return true;
     }
     if (use_xor) return false;
-    switch (vw) {
-        case 4: go<4, true, false>(p, grid, st); return true;
-        case 2: go<2, true, false>(p, grid, st); return true;
-        case 1: go<1, true, false>(p, grid, st); return true;
-        default: return false;
-    }
+    // narrower loader vectors need more loader slots than the 8 x 8 register budget allows
+    if (vw != 4) return false;
+    go<4, true, false>(p, grid, st);
+    return true;
 }
 
 }  // namespace apnn

@@ -64,7 +64,7 @@ struct TileParams {
     uint32_t *out;       // packed codes [M][q_out][NW] or nullptr
     int q_out;
     int NW;              // words per plane row of res/out: N / 32
-    int xcd_remap;       // grid is a multiple of 8: spread logical tiles per XCD
+    int xm, xn;          // 8 XCDs arranged as an xm x xn grid of tile regions (0: plain order)
 };
 
 template <int VW> struct VecT;
@@ -81,19 +81,52 @@ __device__ __forceinline__ int vec_popc(uint4 v) { return __popc(v.x) + __popc(v
 __device__ __forceinline__ int vec_popc(uint2 v) { return __popc(v.x) + __popc(v.y); }
 __device__ __forceinline__ int vec_popc(uint32_t v) { return __popc(v); }
 
-// LDS word offset of tile row r: KC words per row plus one 16-byte pad after
-// every RR rows, so that the 16 threads of a half-row group (rows tx*RR + j)
-// hit distinct bank groups when they read 16-byte vectors.
-template <int KC, int RR> __device__ __forceinline__ int lds_row(int r) { return r * KC + 4 * (r / RR); }
+// registers -> LDS in pieces of at most LV words (LDS rows are LV-word aligned)
+template <int LV> __device__ __forceinline__ void lds_store(uint32_t *dst, uint4 v)
+{
+    if (LV >= 4) {
+        *reinterpret_cast<uint4 *>(dst) = v;
+    } else {
+        *reinterpret_cast<uint2 *>(dst) = make_uint2(v.x, v.y);
+        *reinterpret_cast<uint2 *>(dst + 2) = make_uint2(v.z, v.w);
+    }
+}
+template <int LV> __device__ __forceinline__ void lds_store(uint32_t *dst, uint2 v) { *reinterpret_cast<uint2 *>(dst) = v; }
+template <int LV> __device__ __forceinline__ void lds_store(uint32_t *dst, uint32_t v) { *dst = v; }
 
-template <int RA, int RB, int KC, int VW, bool CONV, bool XOR>
-__global__ __launch_bounds__(256) void tile_kernel(const TileParams p)
+// LV words of one tile row from LDS
+template <int LV> struct LdsVec;
+template <> struct LdsVec<4> {
+    uint32_t w[4];
+    __device__ __forceinline__ void load(const uint32_t *src)
+    {
+        const uint4 v = *reinterpret_cast<const uint4 *>(src);
+        w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
+    }
+};
+template <> struct LdsVec<2> {
+    uint32_t w[2];
+    __device__ __forceinline__ void load(const uint32_t *src)
+    {
+        const uint2 v = *reinterpret_cast<const uint2 *>(src);
+        w[0] = v.x; w[1] = v.y;
+    }
+};
+
+// LDS word offset of tile row r: KC words per row plus LV pad words after every
+// RR rows, so that the 16 threads of a half-row group (rows tx*RR + j) hit
+// distinct banks when they read LV-word vectors.
+template <int KC, int RR, int LV> __device__ __forceinline__ int lds_row(int r) { return r * KC + LV * (r / RR); }
+
+template <int RA, int RB, int KC, int VW, int LV, bool CONV, bool XOR>
+__global__ __launch_bounds__(256, (RA * RB >= 64 ? 2 : 4)) void tile_kernel(const TileParams p)
 {
     constexpr int BM = 16 * RA, BN = 16 * RB;
-    constexpr int CH = KC / VW;                       // vectors per tile row and chunk
+    constexpr int CH = KC / VW;                       // loader vectors per tile row and chunk
     constexpr int A_VECS = BM * CH, B_VECS = BN * CH;
     constexpr int A_SLOTS = (A_VECS + 255) / 256, B_SLOTS = (B_VECS + 255) / 256;
-    constexpr int A_WORDS = BM * KC + 4 * 16, B_WORDS = BN * KC + 4 * 16;
+    constexpr int A_WORDS = BM * KC + LV * 16, B_WORDS = BN * KC + LV * 16;
+    constexpr int NG = KC / LV;                       // LDS read groups per chunk
     using Vec = typename VecT<VW>::type;
 
     __shared__ __attribute__((aligned(16))) uint32_t sA[2][A_WORDS];
@@ -104,262 +137,278 @@ __global__ __launch_bounds__(256) void tile_kernel(const TileParams p)
     const int tid = threadIdx.x;
     const int tx = tid & 15, ty = tid >> 4;
 
-    // ---- block -> tile.  Blocks are dealt round-robin to the 8 XCDs; giving
-    // XCD x the x-th contiguous eighth of the tile list keeps the operand rows a
-    // die works on inside its own L2.
+    // ---- block -> tile.  Blocks are dealt round-robin to the 8 XCDs, each with
+    // its own L2: the tile grid is cut into xm x xn rectangular regions, one per
+    // XCD, so the operand rows a die touches (region rows of A + region columns of
+    // B) stay inside its L2; inside a region tiles run column-fastest.
     const int tilesN = (p.N + BN - 1) / BN;
-    int bid = blockIdx.x;
-    if (p.xcd_remap) bid = (bid & 7) * (gridDim.x >> 3) + (bid >> 3);
-    const int m0 = (bid / tilesN) * BM, n0 = (bid % tilesN) * BN;
+    int tm, tn;
+    if (p.xm > 0) {
+        const int tilesM = (p.M + BM - 1) / BM;
+        const int rm = tilesM / p.xm, rn = tilesN / p.xn;
+        const int xcd = blockIdx.x & 7, tile = blockIdx.x >> 3;
+        tm = (xcd / p.xn) * rm + tile / rn;
+        tn = (xcd % p.xn) * rn + tile % rn;
+    } else {
+        tm = blockIdx.x / tilesN;
+        tn = blockIdx.x % tilesN;
+    }
+    const int m0 = tm * BM, n0 = tn * BN;
 
-    if (tid < BM) sRsA[tid] = 0;
-    if (tid < BN) sRsB[tid] = 0;
+    // Plane pairs are visited diagonal by diagonal, d = s + t from PA+PB-2 down to 0
+    // (within a diagonal s ascending), so that Eq. 1 can be evaluated by Horner's
+    // rule directly in the accumulators: tot = 2*tot when the diagonal changes.
+    const int dmax = p.PA + p.PB - 2;
+    auto first_s = [&](int d) { return max(0, d - (p.PB - 1)); };
+    auto next_pair = [&](int &s_, int &t_) {           // returns true when the diagonal changes
+        if (s_ + 1 < p.PA && t_ - 1 >= 0) { ++s_; --t_; return false; }
+        const int d = s_ + t_ - 1;
+        if (d < 0) return false;
+        s_ = first_s(d); t_ = d - s_;
+        return true;
+    };
+    const int total_it = p.PA * p.PB * p.nk;
 
-    // ---- loader slots: slot u of this thread moves vector v = tid + 256 u
-    int a_row[A_SLOTS], a_off[A_SLOTS];      // tile row, word offset inside chunk
-    int a_h0[A_SLOTS], a_w0[A_SLOTS];        // conv: top-left input coordinate
-    int64_t a_base[A_SLOTS];                 // matrix: word offset of (row, plane 0); conv: pixel index of image start
-    bool a_ok[A_SLOTS];
-#pragma unroll
-    for (int u = 0; u < A_SLOTS; ++u) {
-        const int v = tid + 256 * u;
-        a_row[u] = v / CH;
-        a_off[u] = (v % CH) * VW;
-        const int gm = m0 + a_row[u];
-        a_ok[u] = (v < A_VECS) && (gm < p.M);
+    {
+        if (tid < BM) sRsA[tid] = 0;
+        if (tid < BN) sRsB[tid] = 0;
+
+        // ---- loader: slot u of this thread moves vector v = tid + 256 u of the tile:
+        // tile row v / CH, words (v % CH) * VW .. + VW of the chunk.
+        int a_h0[A_SLOTS], a_w0[A_SLOTS], a_pix[A_SLOTS];      // conv: top-left input coordinate, image base pixel
         if (CONV) {
-            const int wo = gm % p.Wo, ho = (gm / p.Wo) % p.Ho, n = gm / (p.Wo * p.Ho);
-            a_h0[u] = ho * p.stride - p.pad;
-            a_w0[u] = wo * p.stride - p.pad;
-            a_base[u] = static_cast<int64_t>(n) * p.H * p.W;
-        } else {
-            a_h0[u] = a_w0[u] = 0;
-            a_base[u] = static_cast<int64_t>(gm) * p.PA * p.ldwA;
-        }
-    }
-    int b_row[B_SLOTS], b_off[B_SLOTS];
-    int64_t b_base[B_SLOTS];
-    bool b_ok[B_SLOTS];
 #pragma unroll
-    for (int u = 0; u < B_SLOTS; ++u) {
-        const int v = tid + 256 * u;
-        b_row[u] = v / CH;
-        b_off[u] = (v % CH) * VW;
-        const int gn = n0 + b_row[u];
-        b_ok[u] = (v < B_VECS) && (gn < p.N);
-        b_base[u] = static_cast<int64_t>(gn) * p.PB * p.ldwB;
-    }
-
-    auto load_a = [&](int u, int s, int k0) -> Vec {
-        Vec v = vec_zero<VW>();
-        const int kk = k0 + a_off[u];
-        if (a_ok[u] && kk < p.Kw) {
-            if (CONV) {
-                const int tap = static_cast<int>((static_cast<float>(kk) + 0.5f) * p.invCw);
-                const int cw = kk - tap * p.Cw;
-                const int r = tap / p.S, sc = tap - r * p.S;
-                const int h = a_h0[u] + r, w = a_w0[u] + sc;
-                if (h >= 0 && h < p.H && w >= 0 && w < p.W) {
-                    const int64_t pix = a_base[u] + static_cast<int64_t>(h) * p.W + w;
-                    v = *reinterpret_cast<const Vec *>(p.A + (pix * p.PA + s) * p.Cw + cw);
-                }
-            } else {
-                v = *reinterpret_cast<const Vec *>(p.A + a_base[u] + static_cast<int64_t>(s) * p.ldwA + kk);
+            for (int u = 0; u < A_SLOTS; ++u) {
+                const int gm = m0 + (tid + 256 * u) / CH;
+                const int wo = gm % p.Wo, ho = (gm / p.Wo) % p.Ho, n = gm / (p.Wo * p.Ho);
+                a_h0[u] = ho * p.stride - p.pad;
+                a_w0[u] = wo * p.stride - p.pad;
+                a_pix[u] = n * p.H * p.W;
             }
         }
-        return v;
-    };
-    auto load_b = [&](int u, int t, int k0) -> Vec {
-        Vec v = vec_zero<VW>();
-        const int kk = k0 + b_off[u];
-        if (b_ok[u] && kk < p.Kw) v = *reinterpret_cast<const Vec *>(p.B + b_base[u] + static_cast<int64_t>(t) * p.ldwB + kk);
-        return v;
-    };
+        auto load_a = [&](int u, int s, int k0) -> Vec {
+            Vec v = vec_zero<VW>();
+            const int vi = tid + 256 * u;
+            const int gm = m0 + vi / CH, kk = k0 + (vi % CH) * VW;
+            if (vi < A_VECS && gm < p.M && kk < p.Kw) {
+                if (CONV) {
+                    const int tap = static_cast<int>((static_cast<float>(kk) + 0.5f) * p.invCw);
+                    const int cw = kk - tap * p.Cw;
+                    const int r = tap / p.S, sc = tap - r * p.S;
+                    const int h = a_h0[u] + r, w = a_w0[u] + sc;
+                    if (h >= 0 && h < p.H && w >= 0 && w < p.W) {
+                        const int64_t pix = a_pix[u] + h * p.W + w;
+                        v = *reinterpret_cast<const Vec *>(p.A + (pix * p.PA + s) * p.Cw + cw);
+                    }
+                } else {
+                    v = *reinterpret_cast<const Vec *>(p.A + (static_cast<int64_t>(gm) * p.PA + s) * p.ldwA + kk);
+                }
+            }
+            return v;
+        };
+        auto load_b = [&](int u, int t, int k0) -> Vec {
+            Vec v = vec_zero<VW>();
+            const int vi = tid + 256 * u;
+            const int gn = n0 + vi / CH, kk = k0 + (vi % CH) * VW;
+            if (vi < B_VECS && gn < p.N && kk < p.Kw)
+                v = *reinterpret_cast<const Vec *>(p.B + (static_cast<int64_t>(gn) * p.PB + t) * p.ldwB + kk);
+            return v;
+        };
 
-    int tot[RA][RB], acc[RA][RB];
+        int tot[RA][RB];
 #pragma unroll
-    for (int i = 0; i < RA; ++i)
+        for (int i = 0; i < RA; ++i)
 #pragma unroll
-        for (int j = 0; j < RB; ++j) tot[i][j] = acc[i][j] = 0;
-    int rsA[A_SLOTS], rsB[B_SLOTS];
+            for (int j = 0; j < RB; ++j) tot[i][j] = 0;
+        int rsA[A_SLOTS], rsB[B_SLOTS];
 #pragma unroll
-    for (int u = 0; u < A_SLOTS; ++u) rsA[u] = 0;
+        for (int u = 0; u < A_SLOTS; ++u) rsA[u] = 0;
 #pragma unroll
-    for (int u = 0; u < B_SLOTS; ++u) rsB[u] = 0;
+        for (int u = 0; u < B_SLOTS; ++u) rsB[u] = 0;
 
-    const int total_it = p.PA * p.PB * p.nk;
-    Vec ra[A_SLOTS], rb[B_SLOTS];
-
-    // plane pair / chunk of the tile being fetched
-    int fs = 0, ft = 0, fk = 0;
-    auto fetch = [&]() {
+        Vec ra[A_SLOTS], rb[B_SLOTS];
+        int fs = first_s(dmax), ft = dmax - fs, fk = 0;   // plane pair / chunk being fetched
+        int ls = 0, lt = 0;                               // plane pair of the tile held in ra/rb
+        auto fetch = [&]() {                   // issue the global loads only; nothing waits on them here
 #pragma unroll
-        for (int u = 0; u < A_SLOTS; ++u) {
-            ra[u] = load_a(u, fs, fk * KC);
-            if (p.uA != 0 && ft == 0) rsA[u] += vec_popc(ra[u]) << fs;
+            for (int u = 0; u < A_SLOTS; ++u) ra[u] = load_a(u, fs, fk * KC);
+#pragma unroll
+            for (int u = 0; u < B_SLOTS; ++u) rb[u] = load_b(u, ft, fk * KC);
+            ls = fs; lt = ft;
+            if (++fk == p.nk) { fk = 0; next_pair(fs, ft); }
+        };
+        auto stage = [&](int buf) {            // registers -> LDS, plus the row-sum popcounts (J X term)
+            if (p.uA != 0 && lt == 0) {
+#pragma unroll
+                for (int u = 0; u < A_SLOTS; ++u) rsA[u] += vec_popc(ra[u]) << ls;
+            }
+            if (p.uB != 0 && ls == 0) {
+#pragma unroll
+                for (int u = 0; u < B_SLOTS; ++u) rsB[u] += vec_popc(rb[u]) << lt;
+            }
+#pragma unroll
+            for (int u = 0; u < A_SLOTS; ++u) {
+                const int vi = tid + 256 * u;
+                if (vi < A_VECS) lds_store<LV>(&sA[buf][lds_row<KC, RA, LV>(vi / CH) + (vi % CH) * VW], ra[u]);
+            }
+#pragma unroll
+            for (int u = 0; u < B_SLOTS; ++u) {
+                const int vi = tid + 256 * u;
+                if (vi < B_VECS) lds_store<LV>(&sB[buf][lds_row<KC, RB, LV>(vi / CH) + (vi % CH) * VW], rb[u]);
+            }
+        };
+
+        if (total_it > 0) {
+            fetch();
+            stage(0);
         }
+        __syncthreads();
+
+        int cs = first_s(dmax), ct = dmax - cs, ck = 0;   // plane pair / chunk being computed
+        for (int it = 0; it < total_it; ++it) {
+            const int buf = it & 1;
+            if (it + 1 < total_it) fetch();    // global loads for the next chunk fly during the compute below
+
+            const int words = min(KC, p.Kw - ck * KC);
+            const int ng = (words + LV - 1) / LV;
+            const uint32_t *pa = &sA[buf][lds_row<KC, RA, LV>(ty * RA)];
+            const uint32_t *pb = &sB[buf][lds_row<KC, RB, LV>(tx * RB)];
+            // register double buffer over LV-word groups: the LDS reads of group g+1
+            // are issued before the AND/popcount block of group g
+            LdsVec<LV> a[2][RA], b[2][RB];
 #pragma unroll
-        for (int u = 0; u < B_SLOTS; ++u) {
-            rb[u] = load_b(u, ft, fk * KC);
-            if (p.uB != 0 && fs == 0) rsB[u] += vec_popc(rb[u]) << ft;
+            for (int i = 0; i < RA; ++i) a[0][i].load(pa + i * KC);
+#pragma unroll
+            for (int j = 0; j < RB; ++j) b[0][j].load(pb + j * KC);
+#pragma unroll
+            for (int g = 0; g < NG; ++g) {
+                if (g < ng) {
+                    const int cur = g & 1, nxt = cur ^ 1;
+                    if (g + 1 < NG && g + 1 < ng) {
+#pragma unroll
+                        for (int i = 0; i < RA; ++i) a[nxt][i].load(pa + i * KC + LV * (g + 1));
+#pragma unroll
+                        for (int j = 0; j < RB; ++j) b[nxt][j].load(pb + j * KC + LV * (g + 1));
+                    }
+#pragma unroll
+                    for (int i = 0; i < RA; ++i)
+#pragma unroll
+                        for (int j = 0; j < RB; ++j)
+#pragma unroll
+                            for (int w = 0; w < LV; ++w)
+                                tot[i][j] += XOR ? __popc(a[cur][i].w[w] ^ b[cur][j].w[w])
+                                                 : __popc(a[cur][i].w[w] & b[cur][j].w[w]);
+                }
+            }
+            if (++ck == p.nk) {                // plane pair finished
+                ck = 0;
+                if (next_pair(cs, ct)) {       // next diagonal: one Horner step of Eq. 1
+#pragma unroll
+                    for (int i = 0; i < RA; ++i)
+#pragma unroll
+                        for (int j = 0; j < RB; ++j) tot[i][j] <<= 1;
+                }
+            }
+            if (it + 1 < total_it) stage(buf ^ 1);
+            __syncthreads();
         }
-        if (++fk == p.nk) { fk = 0; if (++ft == p.PB) { ft = 0; ++fs; } }
-    };
-    auto stage = [&](int buf) {
-#pragma unroll
-        for (int u = 0; u < A_SLOTS; ++u)
-            if (tid + 256 * u < A_VECS) *reinterpret_cast<Vec *>(&sA[buf][lds_row<KC, RA>(a_row[u]) + a_off[u]]) = ra[u];
-#pragma unroll
-        for (int u = 0; u < B_SLOTS; ++u)
-            if (tid + 256 * u < B_VECS) *reinterpret_cast<Vec *>(&sB[buf][lds_row<KC, RB>(b_row[u]) + b_off[u]]) = rb[u];
-    };
 
-    if (total_it > 0) {
-        fetch();
-        stage(0);
-    }
-    __syncthreads();
+        // ---- row sums for the Case III term
+        if (p.uA != 0) {
+#pragma unroll
+            for (int u = 0; u < A_SLOTS; ++u)
+                if (tid + 256 * u < A_VECS && rsA[u] != 0) atomicAdd(&sRsA[(tid + 256 * u) / CH], rsA[u]);
+        }
+        if (p.uB != 0) {
+#pragma unroll
+            for (int u = 0; u < B_SLOTS; ++u)
+                if (tid + 256 * u < B_VECS && rsB[u] != 0) atomicAdd(&sRsB[(tid + 256 * u) / CH], rsB[u]);
+        }
+        __syncthreads();
 
-    int cs = 0, ct = 0, ck = 0;               // plane pair / chunk being computed
-    for (int it = 0; it < total_it; ++it) {
-        const int buf = it & 1;
-        if (it + 1 < total_it) fetch();       // global loads for the next chunk fly during the compute below
+        // ---- epilogue on the register tile
+        const int gn0 = n0 + tx * RB;
+        int colfix[RB];
+#pragma unroll
+        for (int j = 0; j < RB; ++j) colfix[j] = p.uB * sRsB[tx * RB + j] + p.c0;
+        float sc[RB], bi[RB];
+        if (p.scale) {
+#pragma unroll
+            for (int j = 0; j < RB; ++j) {
+                const bool ok = gn0 + j < p.N;
+                sc[j] = ok ? p.scale[gn0 + j] : 0.0f;
+                bi[j] = ok ? p.bias[gn0 + j] : 0.0f;
+            }
+        }
+        constexpr int LPW = 32 / RB;              // lanes that share one packed output word
+        const int wcol = gn0 >> 5;                // word column of this thread's channels
+        const int bit0 = gn0 & 31;
+        const float qmax = static_cast<float>((1 << (p.q_out > 0 ? p.q_out : 1)) - 1);
 
-        const int words = min(KC, p.Kw - ck * KC);
-        const int nch = (words + 3) >> 2;
-        const uint32_t *pa = &sA[buf][lds_row<KC, RA>(ty * RA)];
-        const uint32_t *pb = &sB[buf][lds_row<KC, RB>(tx * RB)];
-        for (int c = 0; c < nch; ++c) {
-            uint4 a[RA], b[RB];
 #pragma unroll
-            for (int i = 0; i < RA; ++i) a[i] = *reinterpret_cast<const uint4 *>(pa + i * KC + 4 * c);
+        for (int i = 0; i < RA; ++i) {
+            const int gm = m0 + ty * RA + i;
+            const bool rok = gm < p.M;
+            const int rowfix = p.uA * sRsA[ty * RA + i];
+            int y[RB];
 #pragma unroll
-            for (int j = 0; j < RB; ++j) b[j] = *reinterpret_cast<const uint4 *>(pb + j * KC + 4 * c);
+            for (int j = 0; j < RB; ++j) y[j] = p.alpha * tot[i][j] + rowfix + colfix[j];
+
+            if (p.Y && rok) {
+                int32_t *dst = p.Y + static_cast<int64_t>(gm) * p.N + gn0;
+                if ((RB % 4 == 0) && (p.N % 4 == 0) && gn0 + RB <= p.N) {
 #pragma unroll
-            for (int i = 0; i < RA; ++i)
+                    for (int j = 0; j < RB; j += 4)
+                        *reinterpret_cast<int4 *>(dst + j) = make_int4(y[j], y[j + 1], y[j + 2], y[j + 3]);
+                } else {
 #pragma unroll
-                for (int j = 0; j < RB; ++j) {
-                    if (XOR) {
-                        acc[i][j] += __popc(a[i].x ^ b[j].x);
-                        acc[i][j] += __popc(a[i].y ^ b[j].y);
-                        acc[i][j] += __popc(a[i].z ^ b[j].z);
-                        acc[i][j] += __popc(a[i].w ^ b[j].w);
-                    } else {
-                        acc[i][j] += __popc(a[i].x & b[j].x);
-                        acc[i][j] += __popc(a[i].y & b[j].y);
-                        acc[i][j] += __popc(a[i].z & b[j].z);
-                        acc[i][j] += __popc(a[i].w & b[j].w);
+                    for (int j = 0; j < RB; ++j)
+                        if (gn0 + j < p.N) dst[j] = y[j];
+                }
+            }
+            if (p.scale) {
+                float t[RB];
+#pragma unroll
+                for (int j = 0; j < RB; ++j) t[j] = __fmaf_rn(sc[j], static_cast<float>(y[j]), bi[j]);
+                if (p.res) {
+                    uint32_t rw[8];
+#pragma unroll
+                    for (int b = 0; b < 8; ++b)
+                        rw[b] = (b < p.q_res && rok && gn0 < p.N)
+                                    ? p.res[(static_cast<int64_t>(gm) * p.q_res + b) * p.NW + wcol] : 0u;
+#pragma unroll
+                    for (int j = 0; j < RB; ++j) {
+                        uint32_t code = 0;
+#pragma unroll
+                        for (int b = 0; b < 8; ++b) code |= ((rw[b] >> (bit0 + j)) & 1u) << b;
+                        t[j] = __fmaf_rn(p.res_scale, static_cast<float>(code), t[j]);
                     }
                 }
-        }
-        if (++ck == p.nk) {                   // plane pair finished: shift-add by 2^(s+t)
-            const int sh = cs + ct;
+                if (p.T && rok) {
 #pragma unroll
-            for (int i = 0; i < RA; ++i)
-#pragma unroll
-                for (int j = 0; j < RB; ++j) { tot[i][j] += acc[i][j] << sh; acc[i][j] = 0; }
-            ck = 0;
-            if (++ct == p.PB) { ct = 0; ++cs; }
-        }
-        if (it + 1 < total_it) stage(buf ^ 1);
-        __syncthreads();
-    }
-
-    // ---- row sums for the Case III term
-    if (p.uA != 0) {
-#pragma unroll
-        for (int u = 0; u < A_SLOTS; ++u)
-            if (tid + 256 * u < A_VECS && rsA[u] != 0) atomicAdd(&sRsA[a_row[u]], rsA[u]);
-    }
-    if (p.uB != 0) {
-#pragma unroll
-        for (int u = 0; u < B_SLOTS; ++u)
-            if (tid + 256 * u < B_VECS && rsB[u] != 0) atomicAdd(&sRsB[b_row[u]], rsB[u]);
-    }
-    __syncthreads();
-
-    // ---- epilogue on the register tile
-    const int gn0 = n0 + tx * RB;
-    int colfix[RB];
-#pragma unroll
-    for (int j = 0; j < RB; ++j) colfix[j] = p.uB * sRsB[tx * RB + j] + p.c0;
-    float sc[RB], bi[RB];
-    if (p.scale) {
-#pragma unroll
-        for (int j = 0; j < RB; ++j) {
-            const bool ok = gn0 + j < p.N;
-            sc[j] = ok ? p.scale[gn0 + j] : 0.0f;
-            bi[j] = ok ? p.bias[gn0 + j] : 0.0f;
-        }
-    }
-    constexpr int LPW = 32 / RB;              // lanes that share one packed output word
-    const int wcol = gn0 >> 5;                // word column of this thread's channels
-    const int bit0 = gn0 & 31;
-    const float qmax = static_cast<float>((1 << (p.q_out > 0 ? p.q_out : 1)) - 1);
-
-#pragma unroll
-    for (int i = 0; i < RA; ++i) {
-        const int gm = m0 + ty * RA + i;
-        const bool rok = gm < p.M;
-        const int rowfix = p.uA * sRsA[ty * RA + i];
-        int y[RB];
-#pragma unroll
-        for (int j = 0; j < RB; ++j) y[j] = p.alpha * tot[i][j] + rowfix + colfix[j];
-
-        if (p.Y && rok) {
-            int32_t *dst = p.Y + static_cast<int64_t>(gm) * p.N + gn0;
-            if ((RB % 4 == 0) && (p.N % 4 == 0) && gn0 + RB <= p.N) {
-#pragma unroll
-                for (int j = 0; j < RB; j += 4)
-                    *reinterpret_cast<int4 *>(dst + j) = make_int4(y[j], y[j + 1], y[j + 2], y[j + 3]);
-            } else {
-#pragma unroll
-                for (int j = 0; j < RB; ++j)
-                    if (gn0 + j < p.N) dst[j] = y[j];
-            }
-        }
-        if (p.scale) {
-            float t[RB];
-#pragma unroll
-            for (int j = 0; j < RB; ++j) t[j] = __fmaf_rn(sc[j], static_cast<float>(y[j]), bi[j]);
-            if (p.res) {
-                uint32_t rw[8];
-#pragma unroll
-                for (int b = 0; b < 8; ++b)
-                    rw[b] = (b < p.q_res && rok && gn0 < p.N)
-                                ? p.res[(static_cast<int64_t>(gm) * p.q_res + b) * p.NW + wcol] : 0u;
-#pragma unroll
-                for (int j = 0; j < RB; ++j) {
-                    uint32_t code = 0;
-#pragma unroll
-                    for (int b = 0; b < 8; ++b) code |= ((rw[b] >> (bit0 + j)) & 1u) << b;
-                    t[j] = __fmaf_rn(p.res_scale, static_cast<float>(code), t[j]);
+                    for (int j = 0; j < RB; ++j)
+                        if (gn0 + j < p.N) p.T[static_cast<int64_t>(gm) * p.N + gn0 + j] = t[j];
                 }
-            }
-            if (p.T && rok) {
+                if (p.out) {
+                    uint32_t code[RB];
 #pragma unroll
-                for (int j = 0; j < RB; ++j)
-                    if (gn0 + j < p.N) p.T[static_cast<int64_t>(gm) * p.N + gn0 + j] = t[j];
-            }
-            if (p.out) {
-                uint32_t code[RB];
+                    for (int j = 0; j < RB; ++j) {
+                        float f = floorf(t[j]);
+                        f = (f >= 0.0f) ? f : 0.0f;
+                        f = (f > qmax) ? qmax : f;
+                        code[j] = (gn0 + j < p.N) ? static_cast<uint32_t>(f) : 0u;
+                    }
 #pragma unroll
-                for (int j = 0; j < RB; ++j) {
-                    float f = floorf(t[j]);
-                    f = (f >= 0.0f) ? f : 0.0f;
-                    f = (f > qmax) ? qmax : f;
-                    code[j] = (gn0 + j < p.N) ? static_cast<uint32_t>(f) : 0u;
-                }
+                    for (int b = 0; b < 8; ++b) {
+                        if (b < p.q_out) {
+                            uint32_t word = 0;
 #pragma unroll
-                for (int b = 0; b < 8; ++b) {
-                    if (b < p.q_out) {
-                        uint32_t word = 0;
+                            for (int j = 0; j < RB; ++j) word |= ((code[j] >> b) & 1u) << (bit0 + j);
 #pragma unroll
-                        for (int j = 0; j < RB; ++j) word |= ((code[j] >> b) & 1u) << (bit0 + j);
-#pragma unroll
-                        for (int msk = 1; msk < LPW; msk <<= 1) word |= __shfl_xor(word, msk, 64);
-                        if ((tx % LPW) == 0 && rok && gn0 < p.N)
-                            p.out[(static_cast<int64_t>(gm) * p.q_out + b) * p.NW + wcol] = word;
+                            for (int msk = 1; msk < LPW; msk <<= 1) word |= __shfl_xor(word, msk, 64);
+                            if ((tx % LPW) == 0 && rok && gn0 < p.N)
+                                p.out[(static_cast<int64_t>(gm) * p.q_out + b) * p.NW + wcol] = word;
+                        }
                     }
                 }
             }

@@ -13,5 +13,9 @@ bool launch_tile4(const TileParams &p, bool conv, int vw, bool use_xor, unsigned
 bool launch_tile2(const TileParams &p, bool conv, int vw, bool use_xor, unsigned grid, hipStream_t st);
 
 constexpr int kTileKC = 16;   // K words staged per chunk
+#ifndef APNN_TILE_LV
+#define APNN_TILE_LV 4
+#endif
+constexpr int kTileLV = APNN_TILE_LV;   // words per LDS read (2: ds_read_b64, 4: ds_read_b128)
 
 }  // namespace apnn
