@@ -28,6 +28,7 @@ if ROOT not in sys.path:
 
 VALU_PEAK_LANE_OPS = 256 * 64 * 2.4e9      # 256 CUs x 64 lanes/clk x 2.4 GHz (32-bit integer vector ops)
 HBM_PEAK = 8.0e12
+MFMA_FP4_PEAK = 10.1e15                    # dense FP4 matrix peak, FLOP/s
 
 
 def log(*a):
@@ -99,20 +100,30 @@ def main():
     if args.copy_probe:
         src = torch.zeros(1 << 28, dtype=torch.uint8, device="cuda")
         B.apnn_probe_copy(src, torch.empty_like(src))
-    for _ in range(args.warmup):
-        step()
+    def timed(steps, warmup):
+        for _ in range(warmup):
+            step()
+        torch.cuda.synchronize()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        t0 = time.perf_counter()
+        for i in range(steps):
+            step(evs[i])
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        kern = np.array([a.elapsed_time(b) for a, b in evs]) * 1e-3
+        return (t1 - t0) / steps, float(kern.mean())
+
+    # headline: the library's own dispatch (FP4 matrix-core kernel for <= 2-bit operands)
+    os.environ.pop("APNN_MFMA", None)
+    sec_per_step, gemm_s = timed(args.steps, args.warmup)
+    flops = wk.effective_ops                                       # 2 M N K multiply-adds on the matrix cores
+    # the AND + popcount kernel on the same workload (the VALU bitwise+popcount roofline)
+    os.environ["APNN_MFMA"] = "0"
+    _, pop_s = timed(max(args.steps // 4, 5), max(args.warmup // 4, 2))
+    os.environ.pop("APNN_MFMA", None)
+    step()                                                         # leave the default path's result in Y
     torch.cuda.synchronize()
-    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(evs[i])
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    sec_per_step = (t1 - t0) / args.steps
-    kern = np.array([a.elapsed_time(b) for a, b in evs]) * 1e-3
-    gemm_s = float(kern.mean())
     lane_ops = 2.0 * wk.M * wk.N * wk.K * wk.p * wk.q / 32.0     # AND + popcount-accumulate per 32 bit-products
-    achieved = lane_ops / gemm_s
 
     # cheap self-check on the timed output (full parity lives in tests/)
     colsum = Y.sum(dim=0, dtype=torch.int64).cpu().numpy()
@@ -130,12 +141,18 @@ def main():
         "config": {"workload": "config1: w1a2 GEMM M=N=K=4096, +-1 weights x unsigned 2-bit activations, int32 out",
                    "step": "apnn_pack(activations) + apnn_gemm", "seeds": [wk.seedW, wk.seedX]},
         "roofline": {
-            "bound": "alu", "kernel": "tile_kernel<4,4,16,4,4,false,false> (64x64 tile, AND)",
-            "achieved": round(achieved / 1e12, 3), "peak": round(VALU_PEAK_LANE_OPS / 1e12, 3),
-            "unit": "T lane-op/s (32-bit VALU: v_and + v_bcnt per 32 bit-products)",
-            "frac": round(achieved / VALU_PEAK_LANE_OPS, 4),
+            "bound": "mfma", "kernel": "mfma_fp4_kernel<PM1,U2> (v_mfma_scale_f32_32x32x64_f8f6f4, FP4 E2M1)",
+            "achieved": round(flops / gemm_s / 1e12, 1), "peak": MFMA_FP4_PEAK / 1e12, "unit": "TFLOP/s",
+            "frac": round(flops / gemm_s / MFMA_FP4_PEAK, 4),
             "kernel_us": round(gemm_s * 1e6, 2),
             "traffic": None,
+        },
+        "roofline_popcount_kernel": {
+            "bound": "alu", "kernel": "tile_kernel<4,4,16,4,4,false,false> (64x64 tile, v_and + v_bcnt), APNN_MFMA=0",
+            "achieved": round(lane_ops / pop_s / 1e12, 3), "peak": round(VALU_PEAK_LANE_OPS / 1e12, 3),
+            "unit": "T lane-op/s (32-bit VALU, 2 lane-ops per 32 bit-products per plane pair)",
+            "frac": round(lane_ops / pop_s / VALU_PEAK_LANE_OPS, 4),
+            "kernel_us": round(pop_s * 1e6, 2), "eff_tops": round(wk.effective_ops / pop_s / 1e12, 1),
         },
     }
 

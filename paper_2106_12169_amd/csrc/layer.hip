@@ -3,6 +3,7 @@
 #include <cstdlib>
 
 #include "common.h"
+#include "mfma_kernel.h"
 #include "tile_launch.h"
 
 namespace apnn {
@@ -22,6 +23,23 @@ static int pick_tile(int64_t M, int64_t N)
     // unit the 32 x 32 tile recovers thread-level parallelism.
     const int64_t tiles4 = ceil_div(M, 64) * ceil_div(N, 64);
     return tiles4 >= 256 ? 4 : 2;
+}
+
+// The FP4 matrix-core kernel applies when both operands have at most two bits,
+// every partial sum stays an exact fp32 integer (K max|a| max|b| < 2^24) and the
+// problem fills 256 x 256 block tiles reasonably; APNN_MFMA=0 forces the
+// AND+popcount kernel, APNN_MFMA=2 the matrix-core kernel whenever it is exact.
+static bool mfma_fp4_eligible(int64_t M, int64_t N, int64_t K, int pa, int pb, apnn_encoding ea, apnn_encoding eb,
+                              int &kindA, int &kindB)
+{
+    const char *e = std::getenv("APNN_MFMA");            // 0: never, 2: whenever exact (tests), default: large problems
+    const int mode = e ? std::atoi(e) : 1;
+    if (mode == 0 || pa > 2 || pb > 2 || K <= 0) return false;
+    kindA = ea == APNN_ENC_PM1 ? OPK_PM1 : (pa == 2 ? OPK_U2 : OPK_U1);
+    kindB = eb == APNN_ENC_PM1 ? OPK_PM1 : (pb == 2 ? OPK_U2 : OPK_U1);
+    const int64_t maxa = kindA == OPK_U2 ? 3 : 1, maxb = kindB == OPK_U2 ? 3 : 1;
+    if (round_up(K, 256) * maxa * maxb >= (int64_t(1) << 24)) return false;
+    return mode == 2 || M * N >= 256 * 256 * 16;
 }
 
 struct Problem {
@@ -175,6 +193,17 @@ extern "C" int apnn_gemm(const uint32_t *W_dev, const uint32_t *X_dev, int32_t *
     if (K > 0 && (!W_dev || !X_dev)) return fail(APNN_ERR_INVALID_ARG, "apnn_gemm: null operand");
     if (!aligned16(W_dev) || !aligned16(X_dev) || !aligned16(Y_dev))
         return fail(APNN_ERR_ALIGNMENT, "apnn_gemm: buffers must be 16-byte aligned");
+    if (int kA, kB; mfma_fp4_eligible(M, N, K, p, q, encW, encX, kA, kB)) {
+        MfmaParams mp{};
+        mp.A = W_dev; mp.B = X_dev; mp.M = static_cast<int>(M); mp.N = static_cast<int>(N);
+        mp.ldwA = mp.ldwB = static_cast<int>(apnn_row_words(K));
+        mp.nk = static_cast<int>(ceil_div(mp.ldwA, 8));
+        // 0 pad bits of two -1/+1 operands multiply to +1 at every padded K position
+        mp.c0 = (kA == OPK_PM1 && kB == OPK_PM1) ? -static_cast<int>(static_cast<int64_t>(mp.nk) * 256 - K) : 0;
+        mp.Y = Y_dev;
+        const int64_t tiles = ceil_div(M, 256) * ceil_div(N, 256);
+        if (launch_mfma_fp4(mp, kA, kB, static_cast<unsigned>(tiles), as_stream(stream))) return check_launch("apnn_gemm");
+    }
     TileParams t{};
     t.A = W_dev; t.B = X_dev;                 // weights supply the rows of Y (W is M x K, Sec. 4.1)
     t.M = static_cast<int>(M); t.N = static_cast<int>(N);
