@@ -3,7 +3,7 @@
 #include <cstdlib>
 
 #include "common.h"
-#include "mfma_kernel.h"
+#include "mfma_launch.h"
 #include "tile_launch.h"
 
 namespace apnn {
@@ -25,23 +25,6 @@ static int pick_tile(int64_t M, int64_t N)
     return tiles4 >= 256 ? 4 : 2;
 }
 
-// The FP4 matrix-core kernel applies when both operands have at most two bits,
-// every partial sum stays an exact fp32 integer (K max|a| max|b| < 2^24) and the
-// problem fills 256 x 256 block tiles reasonably; APNN_MFMA=0 forces the
-// AND+popcount kernel, APNN_MFMA=2 the matrix-core kernel whenever it is exact.
-static bool mfma_fp4_eligible(int64_t M, int64_t N, int64_t K, int pa, int pb, apnn_encoding ea, apnn_encoding eb,
-                              int &kindA, int &kindB)
-{
-    const char *e = std::getenv("APNN_MFMA");            // 0: never, 2: whenever exact (tests), default: large problems
-    const int mode = e ? std::atoi(e) : 1;
-    if (mode == 0 || pa > 2 || pb > 2 || K <= 0) return false;
-    kindA = ea == APNN_ENC_PM1 ? OPK_PM1 : (pa == 2 ? OPK_U2 : OPK_U1);
-    kindB = eb == APNN_ENC_PM1 ? OPK_PM1 : (pb == 2 ? OPK_U2 : OPK_U1);
-    const int64_t maxa = kindA == OPK_U2 ? 3 : 1, maxb = kindB == OPK_U2 ? 3 : 1;
-    if (round_up(K, 256) * maxa * maxb >= (int64_t(1) << 24)) return false;
-    return mode == 2 || M * N >= 256 * 256 * 16;
-}
-
 struct Problem {
     const char *who;
     bool conv;
@@ -49,6 +32,70 @@ struct Problem {
     int PA, PB;
     apnn_encoding encA, encB;
 };
+
+// ---- FP4 matrix-core path --------------------------------------------------------
+// Applies when every partial sum stays an exact fp32 integer
+// (K max|a| max|b| < 2^24), the encodings are ones the kernel has a digit kind
+// for, and (convolution) the channel count allows 8-byte loader vectors.
+// APNN_MFMA=0 forces the AND+popcount kernel (the literal AP-Bit emulation).
+static bool mfma_kind(int planes, apnn_encoding enc, int &kind, int &digits, int64_t &maxabs)
+{
+    if (enc == APNN_ENC_PM1) { kind = OPK_PM1; digits = 1; maxabs = 1; return planes == 1; }
+    kind = planes == 1 ? OPK_U1 : OPK_U2;
+    digits = (planes + 1) / 2;
+    maxabs = (int64_t(1) << planes) - 1;
+    return true;
+}
+
+static int pick_mfma_tile(int64_t M, int64_t N, bool conv)
+{
+    if (const char *e = std::getenv("APNN_MFMA_TILE")) {
+        const int t = std::atoi(e);
+        if (t == 32 || t == 64 || t == 128 || (t == 256 && !conv)) return t;
+    }
+    // largest block tile that still gives most of the 256 compute units a block and
+    // wastes at most a quarter of its area on the ragged edges
+    auto tiles = [&](int t) { return ceil_div(M, t) * ceil_div(N, t); };
+    auto useful = [&](int t) { return static_cast<double>(M) * N / (static_cast<double>(tiles(t)) * t * t); };
+    if (!conv && tiles(256) >= 128 && useful(256) >= 0.75) return 256;
+    if (tiles(128) >= 192 && useful(128) >= 0.75) return 128;
+    if (tiles(64) >= 1024) return 64;
+    return 32;                                  // small layers: one wave tile per block, K split over its waves
+}
+
+// Returns true if the launch was issued (status in rc), false if the path does not apply.
+static bool try_mfma(const Problem &pr, MfmaParams &mp, void *stream, int &rc)
+{
+    const char *e = std::getenv("APNN_MFMA");
+    if (e && std::atoi(e) == 0) return false;
+    int kA, kB;
+    int64_t maxA, maxB;
+    if (!mfma_kind(pr.PA, pr.encA, kA, mp.DA, maxA) || !mfma_kind(pr.PB, pr.encB, kB, mp.DB, maxB)) return false;
+    if (pr.Ktotal <= 0 || round_up(pr.Ktotal, 1024) * maxA * maxB >= (int64_t(1) << 24)) return false;
+    if (pr.conv && (kA == OPK_PM1 || mp.Cw % 2 != 0)) return false;
+    mp.PA = pr.PA; mp.PB = pr.PB;
+    // 0 pad bits of two -1/+1 operands multiply to +1 at every padded K position
+    int t = pick_mfma_tile(pr.M, pr.N, pr.conv);
+    const bool short_k = !pr.conv && mp.Kw <= 8 && t <= 64;      // 8-word chunks: no step multiplies padding
+    if (short_k) t = 64;
+    const int kc = short_k ? 8 : mfma_chunk_words(t);
+    mp.nk = static_cast<int>(ceil_div(mp.Kw, kc));
+    mp.c0 = (kA == OPK_PM1 && kB == OPK_PM1) ? -static_cast<int>(static_cast<int64_t>(mp.nk) * kc * 32 - pr.Ktotal) : 0;
+    const int64_t tiles = ceil_div(pr.M, t) * ceil_div(pr.N, t);
+    if (tiles > 0x7FFFFFFF) return false;
+    const unsigned grid = static_cast<unsigned>(tiles);
+    bool ok;
+    switch (t) {
+        case 256: ok = launch_mfma256(mp, kA, kB, pr.conv, grid, as_stream(stream)); break;
+        case 128: ok = launch_mfma128(mp, kA, kB, pr.conv, grid, as_stream(stream)); break;
+        case 64: ok = short_k ? launch_mfma64_k8(mp, kA, kB, grid, as_stream(stream))
+                              : launch_mfma64(mp, kA, kB, pr.conv, grid, as_stream(stream)); break;
+        default: ok = launch_mfma32(mp, kA, kB, pr.conv, grid, as_stream(stream)); break;
+    }
+    if (!ok) return false;
+    rc = check_launch(pr.who);
+    return true;
+}
 
 static int run_tile(const Problem &pr, TileParams &p, int vw, void *stream)
 {
@@ -91,6 +138,23 @@ static int run_tile(const Problem &pr, TileParams &p, int vw, void *stream)
     }
     if (!ok) return fail(APNN_ERR_UNSUPPORTED, "%s: no kernel instance for this configuration", pr.who);
     return check_launch(pr.who);
+}
+
+// Matrix-core kernel when it applies, AND+popcount kernel otherwise; both read the
+// same operands and write the same outputs.
+static int run_either(const Problem &pr, TileParams &p, int vw, void *stream)
+{
+    MfmaParams mp{};
+    mp.A = p.A; mp.B = p.B; mp.M = p.M; mp.N = p.N;
+    mp.ldwA = p.ldwA; mp.ldwB = p.ldwB; mp.Kw = p.Kw;
+    mp.H = p.H; mp.W = p.W; mp.Cw = p.Cw; mp.R = p.R; mp.S = p.S; mp.stride = p.stride; mp.pad = p.pad;
+    mp.Ho = p.Ho; mp.Wo = p.Wo; mp.invCw = p.invCw;
+    mp.Y = p.Y; mp.T = p.T; mp.scale = p.scale; mp.bias = p.bias;
+    mp.res = p.res; mp.q_res = p.q_res; mp.res_scale = p.res_scale;
+    mp.out = p.out; mp.q_out = p.q_out; mp.NW = p.NW;
+    int rc = APNN_OK;
+    if (try_mfma(pr, mp, stream, rc)) return rc;
+    return run_tile(pr, p, vw, stream);
 }
 
 static int check_desc(const char *who, const apnn_conv_desc &d, bool is_gemm)
@@ -171,7 +235,7 @@ static int layer_impl(const char *who, const apnn_layer_desc &L, const uint32_t 
     }
     p.NW = static_cast<int>(N / 32);
     Problem pr{who, !is_gemm, M, N, is_gemm ? d.Cin : d.Cin * d.R * d.S, p.PA, p.PB, d.encX, d.encW};
-    return run_tile(pr, p, vw, stream);
+    return run_either(pr, p, vw, stream);
 }
 
 }  // namespace apnn
@@ -193,17 +257,6 @@ extern "C" int apnn_gemm(const uint32_t *W_dev, const uint32_t *X_dev, int32_t *
     if (K > 0 && (!W_dev || !X_dev)) return fail(APNN_ERR_INVALID_ARG, "apnn_gemm: null operand");
     if (!aligned16(W_dev) || !aligned16(X_dev) || !aligned16(Y_dev))
         return fail(APNN_ERR_ALIGNMENT, "apnn_gemm: buffers must be 16-byte aligned");
-    if (int kA, kB; mfma_fp4_eligible(M, N, K, p, q, encW, encX, kA, kB)) {
-        MfmaParams mp{};
-        mp.A = W_dev; mp.B = X_dev; mp.M = static_cast<int>(M); mp.N = static_cast<int>(N);
-        mp.ldwA = mp.ldwB = static_cast<int>(apnn_row_words(K));
-        mp.nk = static_cast<int>(ceil_div(mp.ldwA, 8));
-        // 0 pad bits of two -1/+1 operands multiply to +1 at every padded K position
-        mp.c0 = (kA == OPK_PM1 && kB == OPK_PM1) ? -static_cast<int>(static_cast<int64_t>(mp.nk) * 256 - K) : 0;
-        mp.Y = Y_dev;
-        const int64_t tiles = ceil_div(M, 256) * ceil_div(N, 256);
-        if (launch_mfma_fp4(mp, kA, kB, static_cast<unsigned>(tiles), as_stream(stream))) return check_launch("apnn_gemm");
-    }
     TileParams t{};
     t.A = W_dev; t.B = X_dev;                 // weights supply the rows of Y (W is M x K, Sec. 4.1)
     t.M = static_cast<int>(M); t.N = static_cast<int>(N);
@@ -213,7 +266,7 @@ extern "C" int apnn_gemm(const uint32_t *W_dev, const uint32_t *X_dev, int32_t *
     t.Y = Y_dev;
     t.NW = static_cast<int>(N / 32);
     Problem pr{"apnn_gemm", false, M, N, K, p, q, encW, encX};
-    return run_tile(pr, t, 4, stream);
+    return run_either(pr, t, 4, stream);
 }
 
 extern "C" int apnn_conv2d(const apnn_conv_desc *desc, const uint32_t *W_dev, const uint32_t *X_dev, int32_t *Y_dev,

@@ -1,206 +1,423 @@
-// Matrix-core variant of the plane-pair product for operands of at most two
-// bits (the paper's flagship w1a2 case and its neighbours).
+// Matrix-core variant of the arbitrary-precision product: one template serves
+// apnn_gemm, apnn_conv2d and apnn_layer whenever the result is exactly
+// representable in fp32 (K * max|a| * max|b| < 2^24, checked by the host, which
+// otherwise uses the AND+popcount kernel).
 //
 // CDNA4 has no 1-bit matrix instruction, but its FP4 (E2M1) matrix instruction
-// represents exactly the values a 1- or 2-bit operand can take: {0,1,2,3} and
-// {-1,+1}.  The kernel keeps the packed bit-plane operands of the ABI in HBM and
-// in LDS (Sec. 4.2 (a) data organisation, Sec. 4.1 (a) shared-memory caching) and
-// re-composes, per lane and in registers, the planes of 32 consecutive K
-// positions into 32 FP4 codes (Eq. 2 read backwards); one
-// v_mfma_scale_f32_32x32x64_f8f6f4 then performs 32x32x64 multiply-adds.  All
-// products and partial sums are small integers, exact in the fp32 accumulators as
-// long as K * max|a| * max|b| < 2^24 (checked by the host, which otherwise uses
-// the AND+popcount kernel).  Because -1/+1 is encoded directly, Cases II and III
-// of Sec. 3.2 need no XOR and no J-term here; the only correction is for K pad
-// positions when both operands are -1/+1 (0 pad bits read as (-1)(-1) = +1).
+// represents exactly what one or two bit planes of an operand can encode:
+// {0,1,2,3} and {-1,+1}.  The operands stay in the packed bit-plane layouts of
+// the ABI in HBM and in LDS (Sec. 4.2 (a) data organisation, Sec. 4.1 (a)
+// shared-memory caching).  An operand of more than two bits is cut into base-4
+// digits of two adjacent planes (a last single plane counts as a digit with a
+// zero upper plane); every digit pair (da, db) is one pass over K, and the passes
+// are combined as in Eq. 1 with weights 4^(da+db), evaluated by Horner's rule
+// directly in the accumulators (acc *= 4 whenever the digit diagonal da + db
+// drops by one).  This is the AP-Bit template of Sec. 3.1 with a 2-bit instead of
+// a 1-bit primitive.  Per lane and in registers, the planes of 32 consecutive K
+// positions are re-composed into 32 FP4 codes (Eq. 2 read backwards) and one
+// v_mfma_scale_f32_32x32x64_f8f6f4 performs 32 x 32 x 64 multiply-adds.  All
+// products and partial sums are small integers, hence exact in fp32.  Because
+// -1/+1 is encoded directly, Cases II and III of Sec. 3.2 need no XOR and no
+// J-term here; the only correction is for K pad positions when both operands are
+// -1/+1 (0 pad bits read as (-1)(-1) = +1).
 //
-// Geometry: 256 threads = 4 waves (2 x 2), block tile 256 x 256, wave tile
-// 128 x 128 = 4 x 4 matrix-instruction tiles (256 fp32 accumulators per lane).
-// A K chunk is KC = 8 words = 256 K positions = 4 matrix-instruction steps; the
-// summation order over K is free, so lane-half h of a step takes word
-// (h*KC/2 + step) of the chunk, which lets every lane fetch its four steps of one
-// (row, plane) with a single 16-byte LDS read.
+// Geometry: NWM x NWN waves share a (NWM*FM*32) x (NWN*FN*32) block tile, each
+// wave owning FM x FN matrix-instruction tiles of 32 x 32 (16 fp32 accumulators
+// per lane each).  For small layers a block instead owns a single wave tile and
+// its NSPLIT waves split the K steps of every chunk between them (partial tiles
+// are added through LDS), which shortens the serial instruction stream per wave.  A K chunk is KC words (8 or 32) = KC/2 instruction steps; the summation order over K is free, so lane-half h of a step takes word
+// (h*KC/2 + step) of the chunk, which lets every lane fetch its steps of one
+// (row, plane) with 16-byte LDS reads.  Small problems use the longer chunk so
+// that the exposed memory latency per chunk is paid fewer times.  Global loads of the next chunk
+// fly while the current one is computed (LDS double buffer, one barrier per
+// chunk).  In convolution mode the A rows are output pixels and the K index runs
+// over (kernel row, kernel column, channel word) with zero words for taps outside
+// the frame (Sec. 4.2 (b)).
+//
+// Epilogue (Sec. 4.1 (b), Sec. 5.2): accumulator register r of lane (half lh,
+// column lr) of a 32 x 32 tile is row 8*(r/4) + 4*lh + r%4, column lr.  Lanes are
+// output channels, so the requantised codes of 32 channels are packed with one
+// wave ballot per plane: the low half of the ballot is the word of row(lh=0), the
+// high half that of row(lh=1).
 #pragma once
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <type_traits>
+
+#include "vec_util.h"
 
 namespace apnn {
 
 typedef int v8i_t __attribute__((ext_vector_type(8)));
 typedef float v16f_t __attribute__((ext_vector_type(16)));
 
-enum { OPK_U1 = 0, OPK_U2 = 1, OPK_PM1 = 2 };   // operand kinds
+enum { OPK_U1 = 0, OPK_U2 = 1, OPK_PM1 = 2 };   // digit kinds: one 0/1 plane, two 0/1 planes, one -1/+1 plane
 
 struct MfmaParams {
-    const uint32_t *A, *B;   // row / column operand planes, matrix layout
+    const uint32_t *A, *B;   // row / column operand planes
     int M, N;
-    int ldwA, ldwB;          // words per plane row
-    int nk;                  // K chunks of 8 words
+    int PA, PB;              // planes in memory
+    int DA, DB;              // base-4 digits (ceil(planes / 2); 1 for single-plane kinds)
+    int ldwA, ldwB;          // words per plane row (A: matrix mode only)
+    int Kw;                  // words per plane along K
+    int nk;                  // K chunks of KC words
     int c0;                  // additive correction (pad positions of a -1/+1 x -1/+1 product)
-    int32_t *Y;              // [M][N] int32
+    // convolution geometry of the A operand (conv mode only)
+    int H, W, Cw, R, S, stride, pad, Ho, Wo;
+    float invCw;
+    // outputs, as in the AND+popcount kernel
+    int32_t *Y;
+    float *T;
+    const float *scale, *bias;
+    const uint32_t *res;
+    int q_res;
+    float res_scale;
+    uint32_t *out;
+    int q_out;
+    int NW;
 };
 
-__device__ __forceinline__ uint32_t rotr(uint32_t x, int s) { return __builtin_amdgcn_alignbit(x, x, s); }
+// A 32-bit constant the optimiser cannot fold: it then lives in a register, so
+// that (x & mask) | other compiles to one three-operand instruction instead of
+// two instructions with one literal each.
+__device__ __forceinline__ uint32_t reg_const(uint32_t k)
+{
+    asm volatile("" : "+v"(k));
+    return k;
+}
+
+struct Fp4Masks { uint32_t m1, m2, m4, m8; };
 
 // 32 K positions of one operand row -> 4 dwords of 8 FP4 codes; nibble i of
-// dword r holds the element at bit (r + 4 i) of the plane words.
-template <int KIND> __device__ __forceinline__ void expand_fp4(const uint32_t *w, int stride, v8i_t &out)
+// dword r holds the element at bit (r + 4 i) of the plane words x0 (x1).
+template <int KIND> __device__ __forceinline__ void expand_fp4(uint32_t x0, uint32_t x1, const Fp4Masks &k, v8i_t &out)
 {
     if (KIND == OPK_U1) {                       // 0 -> 0000 (0.0), 1 -> 0010 (1.0)
-        const uint32_t x = w[0];
-        out[0] = rotr(x, 31) & 0x22222222u;
-        out[1] = x & 0x22222222u;
-        out[2] = rotr(x, 1) & 0x22222222u;
-        out[3] = rotr(x, 2) & 0x22222222u;
+        out[0] = (x0 << 1) & k.m2;
+        out[1] = x0 & k.m2;
+        out[2] = (x0 >> 1) & k.m2;
+        out[3] = (x0 >> 2) & k.m2;
     } else if (KIND == OPK_PM1) {               // 1 -> 0010 (+1.0), 0 -> 1010 (-1.0)
-        const uint32_t nx = ~w[0];
-        out[0] = (rotr(nx, 29) & 0x88888888u) | 0x22222222u;
-        out[1] = (rotr(nx, 30) & 0x88888888u) | 0x22222222u;
-        out[2] = (rotr(nx, 31) & 0x88888888u) | 0x22222222u;
-        out[3] = (nx & 0x88888888u) | 0x22222222u;
+        out[0] = (~(x0 << 3) & k.m8) | k.m2;
+        out[1] = (~(x0 << 2) & k.m8) | k.m2;
+        out[2] = (~(x0 << 1) & k.m8) | k.m2;
+        out[3] = (~x0 & k.m8) | k.m2;
     } else {                                    // 0,1,2,3 -> 0000, 0010, 0100, 0101
-        const uint32_t x0 = w[0], x1 = w[stride];
-        const uint32_t m0 = x0 & x1, m1 = x0 ^ m0, m2 = x1;
-        out[0] = (rotr(m2, 30) & 0x44444444u) | (rotr(m1, 31) & 0x22222222u) | (m0 & 0x11111111u);
-        out[1] = (rotr(m2, 31) & 0x44444444u) | (m1 & 0x22222222u) | (rotr(m0, 1) & 0x11111111u);
-        out[2] = (m2 & 0x44444444u) | (rotr(m1, 1) & 0x22222222u) | (rotr(m0, 2) & 0x11111111u);
-        out[3] = (rotr(m2, 1) & 0x44444444u) | (rotr(m1, 2) & 0x22222222u) | (rotr(m0, 3) & 0x11111111u);
+        const uint32_t m0 = x0 & x1, m1 = x0 & ~x1;
+        // bit 2 <- x1, bit 1 <- x0 & ~x1, bit 0 <- x0 & x1; bit-field inserts keep bit 3 clear
+        uint32_t t;
+        t = (x1 << 2) & k.m4; t = (t & ~k.m2) | ((m1 << 1) & k.m2); out[0] = (t & ~k.m1) | (m0 & k.m1);
+        t = (x1 << 1) & k.m4; t = (t & ~k.m2) | (m1 & k.m2);        out[1] = (t & ~k.m1) | ((m0 >> 1) & k.m1);
+        t = x1 & k.m4;        t = (t & ~k.m2) | ((m1 >> 1) & k.m2); out[2] = (t & ~k.m1) | ((m0 >> 2) & k.m1);
+        t = (x1 >> 1) & k.m4; t = (t & ~k.m2) | ((m1 >> 2) & k.m2); out[3] = (t & ~k.m1) | ((m0 >> 3) & k.m1);
     }
     out[4] = out[5] = out[6] = out[7] = 0;
 }
 
-template <int KIND> struct OpPlanes { static constexpr int value = (KIND == OPK_U2) ? 2 : 1; };
-
-template <int KA, int KB>
-__global__ __launch_bounds__(256, 1) void mfma_fp4_kernel(const MfmaParams p)
+// f(integral_constant<int, 0>), ..., f(integral_constant<int, N-1>)
+template <int N, class F> __device__ __forceinline__ void static_for(F &&f)
 {
-    constexpr int KC = 8;                               // words per chunk
-    constexpr int PA = OpPlanes<KA>::value, PB = OpPlanes<KB>::value;
-    constexpr int BT = 256;                             // block tile edge
-    constexpr int RSA = PA * KC + 4, RSB = PB * KC + 4; // padded LDS row strides (words)
-    constexpr int A_VECS = BT * PA * 2, B_VECS = BT * PB * 2;   // 16-byte vectors per chunk
-    constexpr int A_SLOTS = A_VECS / 256, B_SLOTS = B_VECS / 256;
+    if constexpr (N > 0) {
+        static_for<N - 1>(f);
+        f(std::integral_constant<int, N - 1>{});
+    }
+}
 
-    __shared__ __attribute__((aligned(16))) uint32_t sA[2][BT * RSA];
-    __shared__ __attribute__((aligned(16))) uint32_t sB[2][BT * RSB];
+template <int KIND> struct DigitPlanes { static constexpr int value = (KIND == OPK_U2) ? 2 : 1; };
+
+template <int KA, int KB, int NWM, int NWN, int NSPLIT, int FM, int FN, int KC, int VW, bool CONV>
+__global__ __launch_bounds__(64 * NWM * NWN * NSPLIT, (NWM * NWN * FM * FN >= 64 && FM * FN >= 16) ? 1 : 2)
+void mfma_fp4_kernel(const MfmaParams p)
+{
+    static_assert(NSPLIT == 1 || (NWM == 1 && NWN == 1), "K is split across the waves of a single-tile block only");
+    constexpr int NT = 64 * NWM * NWN * NSPLIT;         // threads
+    constexpr int NS = KC / 2;                          // matrix-instruction steps per chunk
+    constexpr int NSW = NS / NSPLIT;                    // ... of which each wave of a K-split block takes NSW
+    static_assert(NSW % 4 == 0, "a wave reads its steps with 16-byte LDS loads");
+    constexpr int LA = DigitPlanes<KA>::value, LB = DigitPlanes<KB>::value;   // planes of one digit
+    constexpr int BM = NWM * FM * 32, BN = NWN * FN * 32;
+    constexpr int RSA = LA * KC + 4, RSB = LB * KC + 4; // padded LDS row strides (words)
+    constexpr int CH = KC / VW;                         // loader vectors per (row, plane) and chunk
+    constexpr int A_VECS = BM * LA * CH, B_VECS = BN * LB * (KC / 4);
+    constexpr int A_SLOTS = (A_VECS + NT - 1) / NT, B_SLOTS = (B_VECS + NT - 1) / NT;
+    using VecA = typename VecT<VW>::type;
+
+    // one LDS arena: the double-buffered operand tiles; in a K-split block the
+    // reduction buffer reuses it once the main loop is over
+    constexpr int TILE_WORDS = 2 * BM * RSA + 2 * BN * RSB;
+    constexpr int RED_WORDS = NSPLIT > 1 ? NSPLIT * FM * FN * 16 * 64 : 0;
+    __shared__ __attribute__((aligned(16))) uint32_t smem[TILE_WORDS > RED_WORDS ? TILE_WORDS : RED_WORDS];
+    uint32_t (*sA)[BM * RSA] = reinterpret_cast<uint32_t (*)[BM * RSA]>(smem);
+    uint32_t (*sB)[BN * RSB] = reinterpret_cast<uint32_t (*)[BN * RSB]>(smem + 2 * BM * RSA);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;            // wave position in the 2 x 2 arrangement
+    const int ks = wave / (NWM * NWN);                  // K-split index of this wave
+    const int wm = (wave % (NWM * NWN)) / NWN, wn = wave % NWN;   // wave position in the NWM x NWN arrangement
     const int lr = lane & 31, lh = lane >> 5;           // row / column inside a 32-wide tile, K half
 
-    const int tilesN = (p.N + BT - 1) / BT;
-    const int m0 = (blockIdx.x / tilesN) * BT, n0 = (blockIdx.x % tilesN) * BT;
+    const int tilesN = (p.N + BN - 1) / BN;
+    const int m0 = (blockIdx.x / tilesN) * BM, n0 = (blockIdx.x % tilesN) * BN;
 
-    // loader: vector v = tid + 256 u covers (row, plane, half-chunk c): v = (row*P + plane)*2 + c
-    uint4 ra[A_SLOTS], rb[B_SLOTS];
-    auto fetch = [&](int kc) {
+    Fp4Masks km;
+    km.m1 = reg_const(0x11111111u); km.m2 = reg_const(0x22222222u);
+    km.m4 = reg_const(0x44444444u); km.m8 = reg_const(0x88888888u);
+
+    // ---- loader.  A vector v = tid + NT u covers (row, plane of the digit, piece c):
+    // v = (row * LA + pl) * CH + c; B likewise with 16-byte pieces.
+    int a_h0[A_SLOTS], a_w0[A_SLOTS], a_pix[A_SLOTS];
+    if (CONV) {
 #pragma unroll
         for (int u = 0; u < A_SLOTS; ++u) {
-            const int v = tid + 256 * u, c = v & 1, rp = v >> 1;
-            const int row = rp / PA, pl = rp % PA, kk = kc * KC + 4 * c;
-            ra[u] = make_uint4(0, 0, 0, 0);
-            if (m0 + row < p.M && kk < p.ldwA)
-                ra[u] = *reinterpret_cast<const uint4 *>(p.A + (static_cast<int64_t>(m0 + row) * PA + pl) * p.ldwA + kk);
+            const int gm = m0 + (tid + NT * u) / (LA * CH);
+            const int wo = gm % p.Wo, ho = (gm / p.Wo) % p.Ho, n = gm / (p.Wo * p.Ho);
+            a_h0[u] = ho * p.stride - p.pad;
+            a_w0[u] = wo * p.stride - p.pad;
+            a_pix[u] = n * p.H * p.W;
+        }
+    }
+    VecA ra[A_SLOTS];
+    uint4 rb[B_SLOTS];
+    auto fetch = [&](int da, int db, int kc) {
+#pragma unroll
+        for (int u = 0; u < A_SLOTS; ++u) {
+            const int v = tid + NT * u, c = v % CH, rp = v / CH;
+            const int row = rp / LA, plane = 2 * da * (LA - 1) + da * (2 - LA) + rp % LA;   // LA = 2: 2 da + pl; LA = 1: da
+            const int gm = m0 + row, kk = kc * KC + c * VW;
+            ra[u] = vec_zero<VW>();
+            if (v < A_VECS && gm < p.M && kk < p.Kw && plane < p.PA) {
+                if (CONV) {
+                    const int tap = static_cast<int>((static_cast<float>(kk) + 0.5f) * p.invCw);
+                    const int cw = kk - tap * p.Cw;
+                    const int r = tap / p.S, sc = tap - r * p.S;
+                    const int h = a_h0[u] + r, w = a_w0[u] + sc;
+                    if (h >= 0 && h < p.H && w >= 0 && w < p.W) {
+                        const int64_t pix = a_pix[u] + h * p.W + w;
+                        ra[u] = *reinterpret_cast<const VecA *>(p.A + (pix * p.PA + plane) * p.Cw + cw);
+                    }
+                } else {
+                    ra[u] = *reinterpret_cast<const VecA *>(p.A + (static_cast<int64_t>(gm) * p.PA + plane) * p.ldwA + kk);
+                }
+            }
         }
 #pragma unroll
         for (int u = 0; u < B_SLOTS; ++u) {
-            const int v = tid + 256 * u, c = v & 1, rp = v >> 1;
-            const int row = rp / PB, pl = rp % PB, kk = kc * KC + 4 * c;
+            const int v = tid + NT * u, c = v % (KC / 4), rp = v / (KC / 4);
+            const int row = rp / LB, plane = 2 * db * (LB - 1) + db * (2 - LB) + rp % LB;
+            const int gn = n0 + row, kk = kc * KC + 4 * c;
             rb[u] = make_uint4(0, 0, 0, 0);
-            if (n0 + row < p.N && kk < p.ldwB)
-                rb[u] = *reinterpret_cast<const uint4 *>(p.B + (static_cast<int64_t>(n0 + row) * PB + pl) * p.ldwB + kk);
+            if (v < B_VECS && gn < p.N && kk < p.Kw && plane < p.PB) {
+                const uint32_t *src = p.B + (static_cast<int64_t>(gn) * p.PB + plane) * p.ldwB + kk;
+                if (!CONV) {
+                    rb[u] = *reinterpret_cast<const uint4 *>(src);
+                } else {                        // conv weight rows are 8-byte aligned and an even number of words long
+                    const uint2 lo = *reinterpret_cast<const uint2 *>(src);
+                    uint2 hi = make_uint2(0, 0);
+                    if (kk + 4 <= p.Kw) hi = *reinterpret_cast<const uint2 *>(src + 2);
+                    rb[u] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+                }
+            }
         }
     };
     auto stage = [&](int buf) {
 #pragma unroll
         for (int u = 0; u < A_SLOTS; ++u) {
-            const int v = tid + 256 * u, c = v & 1, rp = v >> 1;
-            *reinterpret_cast<uint4 *>(&sA[buf][(rp / PA) * RSA + (rp % PA) * KC + 4 * c]) = ra[u];
+            const int v = tid + NT * u, c = v % CH, rp = v / CH;
+            if (v < A_VECS) *reinterpret_cast<VecA *>(&sA[buf][(rp / LA) * RSA + (rp % LA) * KC + c * VW]) = ra[u];
         }
 #pragma unroll
         for (int u = 0; u < B_SLOTS; ++u) {
-            const int v = tid + 256 * u, c = v & 1, rp = v >> 1;
-            *reinterpret_cast<uint4 *>(&sB[buf][(rp / PB) * RSB + (rp % PB) * KC + 4 * c]) = rb[u];
+            const int v = tid + NT * u, c = v % (KC / 4), rp = v / (KC / 4);
+            if (v < B_VECS) *reinterpret_cast<uint4 *>(&sB[buf][(rp / LB) * RSB + (rp % LB) * KC + 4 * c]) = rb[u];
         }
     };
 
-    v16f_t acc[4][4];
+    v16f_t acc[FM][FN];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < FM; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < FN; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    if (p.nk > 0) {
-        fetch(0);
+    // digit pairs diagonal by diagonal (da + db descending), as the plane pairs of
+    // the AND+popcount kernel, so that Eq. 1 becomes a Horner evaluation in base 4
+    const int dmax = p.DA + p.DB - 2;
+    auto first_a = [&](int d) { return max(0, d - (p.DB - 1)); };
+    auto next_pair = [&](int &a_, int &b_) {
+        if (a_ + 1 < p.DA && b_ - 1 >= 0) { ++a_; --b_; return false; }
+        const int d = a_ + b_ - 1;
+        if (d < 0) return false;
+        a_ = first_a(d); b_ = d - a_;
+        return true;
+    };
+    const int total_it = p.DA * p.DB * p.nk;
+    int fa_ = first_a(dmax), fb_ = dmax - fa_, fk = 0;  // pair / chunk being fetched
+    int ca = fa_, cb = fb_, ck = 0;                     // pair / chunk being computed
+
+    // K-split blocks are latency bound: fetch the epilogue's per-channel parameters
+    // and residual codes now, so that their latency hides behind the main loop
+    constexpr int RPW = 16 / NSPLIT;
+    float pre_sc[FN], pre_bi[FN];
+    uint32_t pre_res[NSPLIT > 1 ? FM * FN * RPW : 1];
+    if constexpr (NSPLIT > 1) {
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+            const int gn = n0 + j * 32 + lr;
+            pre_sc[j] = pre_bi[j] = 0.0f;
+            if (p.scale && gn < p.N) { pre_sc[j] = p.scale[gn]; pre_bi[j] = p.bias[gn]; }
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int rr = 0; rr < RPW; ++rr) {
+                    const int gm = m0 + i * 32 + 8 * ks + 4 * lh + rr;     // accumulator register 4 ks + rr
+                    uint32_t code = 0;
+                    if (p.res && gm < p.M && gn < p.N) {
+                        const uint32_t *rp = p.res + static_cast<int64_t>(gm) * p.q_res * p.NW + (gn >> 5);
+                        for (int b = 0; b < p.q_res; ++b) code |= ((rp[b * p.NW] >> lr) & 1u) << b;
+                    }
+                    pre_res[(i * FN + j) * RPW + rr] = code;
+                }
+        }
+    }
+
+    if (total_it > 0) {
+        fetch(fa_, fb_, 0);
+        if (++fk == p.nk) { fk = 0; next_pair(fa_, fb_); }
         stage(0);
     }
     __syncthreads();
 
-    for (int kc = 0; kc < p.nk; ++kc) {
-        const int buf = kc & 1;
-        if (kc + 1 < p.nk) fetch(kc + 1);
+    for (int it = 0; it < total_it; ++it) {
+        const int buf = it & 1;
+        if (it + 1 < total_it) {
+            fetch(fa_, fb_, fk);
+            if (++fk == p.nk) { fk = 0; next_pair(fa_, fb_); }
+        }
 
-        // this lane's words of the chunk: 4 steps x planes, for its 4 + 4 tile rows
-        uint32_t wa[4][PA][4], wb[4][PB][4];
+        // this lane's words of the chunk: NS steps x planes of the digit, for its tile rows
+        uint32_t wa[FM][LA][NSW], wb[FN][LB][NSW];
 #pragma unroll
-        for (int f = 0; f < 4; ++f)
+        for (int f = 0; f < FM; ++f)
 #pragma unroll
-            for (int pl = 0; pl < PA; ++pl) {
-                const uint4 v = *reinterpret_cast<const uint4 *>(&sA[buf][(wm * 128 + f * 32 + lr) * RSA + pl * KC + 4 * lh]);
-                wa[f][pl][0] = v.x; wa[f][pl][1] = v.y; wa[f][pl][2] = v.z; wa[f][pl][3] = v.w;
-            }
+            for (int pl = 0; pl < LA; ++pl)
 #pragma unroll
-        for (int f = 0; f < 4; ++f)
+                for (int g = 0; g < NSW / 4; ++g) {
+                    const uint4 v = *reinterpret_cast<const uint4 *>(
+                        &sA[buf][(wm * FM * 32 + f * 32 + lr) * RSA + pl * KC + NS * lh + NSW * ks + 4 * g]);
+                    wa[f][pl][4 * g] = v.x; wa[f][pl][4 * g + 1] = v.y; wa[f][pl][4 * g + 2] = v.z; wa[f][pl][4 * g + 3] = v.w;
+                }
 #pragma unroll
-            for (int pl = 0; pl < PB; ++pl) {
-                const uint4 v = *reinterpret_cast<const uint4 *>(&sB[buf][(wn * 128 + f * 32 + lr) * RSB + pl * KC + 4 * lh]);
-                wb[f][pl][0] = v.x; wb[f][pl][1] = v.y; wb[f][pl][2] = v.z; wb[f][pl][3] = v.w;
-            }
+        for (int f = 0; f < FN; ++f)
 #pragma unroll
-        for (int st = 0; st < 4; ++st) {
-            v8i_t fa[4], fb[4];
+            for (int pl = 0; pl < LB; ++pl)
 #pragma unroll
-            for (int f = 0; f < 4; ++f) {
-                uint32_t t[2];
-                t[0] = wa[f][0][st]; t[1] = wa[f][PA - 1][st];
-                expand_fp4<KA>(t, 1, fa[f]);
-            }
+                for (int g = 0; g < NSW / 4; ++g) {
+                    const uint4 v = *reinterpret_cast<const uint4 *>(
+                        &sB[buf][(wn * FN * 32 + f * 32 + lr) * RSB + pl * KC + NS * lh + NSW * ks + 4 * g]);
+                    wb[f][pl][4 * g] = v.x; wb[f][pl][4 * g + 1] = v.y; wb[f][pl][4 * g + 2] = v.z; wb[f][pl][4 * g + 3] = v.w;
+                }
 #pragma unroll
-            for (int f = 0; f < 4; ++f) {
-                uint32_t t[2];
-                t[0] = wb[f][0][st]; t[1] = wb[f][PB - 1][st];
-                expand_fp4<KB>(t, 1, fb[f]);
-            }
+        for (int st = 0; st < NSW; ++st) {
+            v8i_t fa[FM], fb[FN];
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+            for (int f = 0; f < FM; ++f) expand_fp4<KA>(wa[f][0][st], wa[f][LA - 1][st], km, fa[f]);
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
+            for (int f = 0; f < FN; ++f) expand_fp4<KB>(wb[f][0][st], wb[f][LB - 1][st], km, fb[f]);
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fa[i], fb[j], acc[i][j], 4, 4, 0,
                                                                                  0x7f7f7f7f, 0, 0x7f7f7f7f);
         }
-        if (kc + 1 < p.nk) stage(buf ^ 1);
+        if (++ck == p.nk) {                     // digit pair finished
+            ck = 0;
+            if (next_pair(ca, cb)) {            // next diagonal: one Horner step in base 4
+#pragma unroll
+                for (int i = 0; i < FM; ++i)
+#pragma unroll
+                    for (int j = 0; j < FN; ++j)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) acc[i][j][r] *= 4.0f;
+            }
+        }
+        if (it + 1 < total_it) stage(buf ^ 1);
         __syncthreads();
     }
 
-    // ---- int32 store.  Accumulator register r of lane (lh, lr) in tile (i, j) is
-    // row 8*(r/4) + 4*lh + r%4, column lr of that 32 x 32 tile.
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int gm = m0 + wm * 128 + i * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
-            if (gm < p.M) {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int gn = n0 + wn * 128 + j * 32 + lr;
-                    if (gn < p.N) p.Y[static_cast<int64_t>(gm) * p.N + gn] = static_cast<int>(acc[i][j][r]) + p.c0;
+    // ---- epilogue on one output value: optional int32 store, fused scale/bias,
+    // residual, floor/clamp and the ballot-packed planes (every lane of the wave
+    // takes part; gm differs only between the two lane halves)
+    const float qmax = static_cast<float>((1 << (p.q_out > 0 ? p.q_out : 1)) - 1);
+    auto finish = [&](float v, int gm, int gn, float sc, float bi, bool have_res, uint32_t res_code) {
+        const bool rok = gm < p.M, cok = gn < p.N;
+        const int wcol = gn >> 5;               // word column of this lane's channel (the 32-wide tile shares it)
+        const int y = static_cast<int>(v) + p.c0;
+        if (p.Y && rok && cok) p.Y[static_cast<int64_t>(gm) * p.N + gn] = y;
+        if (p.scale) {
+            float t = __fmaf_rn(sc, static_cast<float>(y), bi);
+            if (p.res) {
+                uint32_t code = res_code;
+                if (!have_res && rok && cok) {
+                    const uint32_t *rp = p.res + static_cast<int64_t>(gm) * p.q_res * p.NW + wcol;
+                    for (int b = 0; b < p.q_res; ++b) code |= ((rp[b * p.NW] >> lr) & 1u) << b;
+                }
+                t = __fmaf_rn(p.res_scale, static_cast<float>(code), t);
+            }
+            if (p.T && rok && cok) p.T[static_cast<int64_t>(gm) * p.N + gn] = t;
+            if (p.out) {
+                float f = floorf(t);
+                f = (f >= 0.0f) ? f : 0.0f;
+                f = (f > qmax) ? qmax : f;
+                const uint32_t code = cok ? static_cast<uint32_t>(f) : 0u;
+                uint32_t *op = p.out + static_cast<int64_t>(gm) * p.q_out * p.NW + wcol;
+                for (int b = 0; b < p.q_out; ++b) {
+                    const unsigned long long bal = __ballot((code >> b) & 1u);
+                    const uint32_t word = lh ? static_cast<uint32_t>(bal >> 32) : static_cast<uint32_t>(bal);
+                    if (lr == 0 && rok && cok) op[b * p.NW] = word;
                 }
             }
         }
+    };
+
+    if constexpr (NSPLIT == 1) {
+        // compile-time indices keep the accumulators in registers
+        static_for<FN>([&](auto jc) {
+            constexpr int j = decltype(jc)::value;
+            const int gn = n0 + wn * FN * 32 + j * 32 + lr;
+            float sc = 0.0f, bi = 0.0f;
+            if (p.scale && gn < p.N) { sc = p.scale[gn]; bi = p.bias[gn]; }
+            static_for<FM * 16>([&](auto irc) {
+                constexpr int i = decltype(irc)::value / 16, r = decltype(irc)::value % 16;
+                finish(acc[i][j][r], m0 + wm * FM * 32 + i * 32 + 8 * (r >> 2) + 4 * lh + (r & 3), gn, sc, bi, false, 0u);
+            });
+        });
+    } else {
+        // K-split block: the waves' partial tiles are added through LDS; wave ks then
+        // finishes accumulator registers 4 ks .. 4 ks + 3, i.e. rows 8 ks .. 8 ks + 7 of
+        // every 32 x 32 tile, so the epilogue work is shared as well.
+        float (*sRed)[FM * FN * 16][64] = reinterpret_cast<float (*)[FM * FN * 16][64]>(smem);   // tiles are dead: the main loop ended with a barrier
+        static_for<FM * FN * 16>([&](auto c) {
+            constexpr int f = decltype(c)::value / 16, r = decltype(c)::value % 16;
+            sRed[ks][f * 16 + r][lane] = acc[f / FN][f % FN][r];
+        });
+        __syncthreads();
+        static_for<FN>([&](auto jc) {
+            constexpr int j = decltype(jc)::value;
+            const int gn = n0 + j * 32 + lr;
+            static_for<FM * RPW>([&](auto irc) {
+                constexpr int i = decltype(irc)::value / RPW, rr = decltype(irc)::value % RPW;
+                const int r = ks * RPW + rr;
+                float v = 0.0f;
+#pragma unroll
+                for (int k = 0; k < NSPLIT; ++k) v += sRed[k][(i * FN + j) * 16 + r][lane];
+                finish(v, m0 + i * 32 + 8 * (r >> 2) + 4 * lh + (r & 3), gn, pre_sc[j], pre_bi[j], true,
+                       pre_res[(i * FN + j) * RPW + rr]);
+            });
+        });
+    }
 }
 
 }  // namespace apnn

@@ -1,0 +1,20 @@
+// Launchers of the FP4 matrix-core kernel instances (one translation unit per
+// block-tile size so they compile in parallel).
+#pragma once
+#include "mfma_kernel.h"
+
+namespace apnn {
+
+// tile: 256 (256 x 256 block, 8 waves), 128 (128 x 128, 4 waves), 64 (64 x 64, 4 waves),
+// 32 (32 x 32, 4 waves splitting K).
+// Returns false if the combination is not instantiated.
+bool launch_mfma256(const MfmaParams &p, int kindA, int kindB, bool conv, unsigned grid, hipStream_t st);
+bool launch_mfma128(const MfmaParams &p, int kindA, int kindB, bool conv, unsigned grid, hipStream_t st);
+bool launch_mfma64(const MfmaParams &p, int kindA, int kindB, bool conv, unsigned grid, hipStream_t st);
+bool launch_mfma64_k8(const MfmaParams &p, int kindA, int kindB, unsigned grid, hipStream_t st);   // K <= 8 words
+bool launch_mfma32(const MfmaParams &p, int kindA, int kindB, bool conv, unsigned grid, hipStream_t st);
+
+// K words per chunk of each tile size (must match the instances).
+constexpr int mfma_chunk_words(int tile) { return tile == 256 ? 8 : tile == 128 ? 16 : 32; }
+
+}  // namespace apnn

@@ -120,7 +120,9 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(const float *__restr
 }
 
 // Input-layer receptive-field packing: word r of an output pixel holds bit
-// (s*C + c) = bit t of image[n][c][ho*stride+r-pad][wo*stride+s-pad].
+// (s*C + c) = bit t of image[n][c][ho*stride+r-pad][wo*stride+s-pad].  The S*C
+// bytes of one kernel row are first collected four to a register; every plane
+// then takes one bit of each byte with the same gather as the row packer.
 __global__ __launch_bounds__(256) void pack_patches_kernel(const uint8_t *__restrict__ img,
                                                            uint32_t *__restrict__ dst, int64_t npix,
                                                            int C, int H, int W, int Ho, int Wo, int R, int S,
@@ -133,23 +135,26 @@ __global__ __launch_bounds__(256) void pack_patches_kernel(const uint8_t *__rest
     const int wo = static_cast<int>(pix % Wo);
     const int ho = static_cast<int>((pix / Wo) % Ho);
     const int64_t n = pix / (static_cast<int64_t>(Wo) * Ho);
-    uint32_t w[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    uint32_t d[8] = {0, 0, 0, 0, 0, 0, 0, 0};        // byte (s*C + c) of the kernel row, 4 per register
     const int h = ho * stride + r - pad;
     if (r < R && h >= 0 && h < H) {
-        for (int s = 0; s < S; ++s) {
-            const int x = wo * stride + s - pad;
-            if (x < 0 || x >= W) continue;
-            for (int c = 0; c < C; ++c) {
-                const uint32_t v = img[((n * C + c) * H + h) * W + x];
+        const int x0 = wo * stride - pad;
 #pragma unroll
-                for (int t = 0; t < 8; ++t)
-                    if (t < bits) w[t] |= ((v >> t) & 1u) << (s * C + c);
-            }
+        for (int i = 0; i < 32; ++i) {
+            const int sc = i / C, c = i - sc * C, x = x0 + sc;   // C is small: the division is cheap integer work
+            if (i < S * C && x >= 0 && x < W)
+                d[i >> 2] |= static_cast<uint32_t>(img[((n * C + c) * H + h) * W + x]) << (8 * (i & 3));
         }
     }
 #pragma unroll
-    for (int t = 0; t < 8; ++t)
-        if (t < bits) dst[(static_cast<size_t>(pix) * bits + t) * ldw + r] = w[t];
+    for (int t = 0; t < 8; ++t) {
+        if (t < bits) {
+            uint32_t w = 0;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) w |= gather4((d[i] >> t) & 0x01010101u) << (4 * i);
+            dst[(static_cast<size_t>(pix) * bits + t) * ldw + r] = w;
+        }
+    }
 }
 
 __global__ __launch_bounds__(256) void pack_patch_weights_kernel(const uint8_t *__restrict__ wsrc,

@@ -39,6 +39,8 @@
 
 #include <cstdint>
 
+#include "vec_util.h"
+
 namespace apnn {
 
 struct TileParams {
@@ -66,20 +68,6 @@ struct TileParams {
     int NW;              // words per plane row of res/out: N / 32
     int xm, xn;          // 8 XCDs arranged as an xm x xn grid of tile regions (0: plain order)
 };
-
-template <int VW> struct VecT;
-template <> struct VecT<4> { using type = uint4; };
-template <> struct VecT<2> { using type = uint2; };
-template <> struct VecT<1> { using type = uint32_t; };
-
-template <int VW> __device__ __forceinline__ typename VecT<VW>::type vec_zero();
-template <> __device__ __forceinline__ uint4 vec_zero<4>() { return make_uint4(0, 0, 0, 0); }
-template <> __device__ __forceinline__ uint2 vec_zero<2>() { return make_uint2(0, 0); }
-template <> __device__ __forceinline__ uint32_t vec_zero<1>() { return 0u; }
-
-__device__ __forceinline__ int vec_popc(uint4 v) { return __popc(v.x) + __popc(v.y) + __popc(v.z) + __popc(v.w); }
-__device__ __forceinline__ int vec_popc(uint2 v) { return __popc(v.x) + __popc(v.y); }
-__device__ __forceinline__ int vec_popc(uint32_t v) { return __popc(v); }
 
 // registers -> LDS in pieces of at most LV words (LDS rows are LV-word aligned)
 template <int LV> __device__ __forceinline__ void lds_store(uint32_t *dst, uint4 v)

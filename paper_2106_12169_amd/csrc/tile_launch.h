@@ -12,10 +12,6 @@ bool launch_tile8(const TileParams &p, bool conv, int vw, bool use_xor, unsigned
 bool launch_tile4(const TileParams &p, bool conv, int vw, bool use_xor, unsigned grid, hipStream_t st);
 bool launch_tile2(const TileParams &p, bool conv, int vw, bool use_xor, unsigned grid, hipStream_t st);
 
-struct MfmaParams;
-// FP4 matrix-core kernel; kind: 0 unsigned 1-bit, 1 unsigned 2-bit, 2 -1/+1.
-bool launch_mfma_fp4(const MfmaParams &p, int kindA, int kindB, unsigned grid, hipStream_t st);
-
 constexpr int kTileKC = 16;   // K words staged per chunk
 #ifndef APNN_TILE_LV
 #define APNN_TILE_LV 4

@@ -1,6 +1,6 @@
-"""GPU parity of the FP4 matrix-core GEMM path (operands of at most two bits)
-against the integer oracle, bit-exact, at sizes that span several K chunks,
-ragged tails in M, N and K, and every operand-kind pair."""
+"""GPU parity of the FP4 matrix-core GEMM path against the integer oracle,
+bit-exact, at sizes that span several K chunks, ragged tails in M, N and K, every
+digit-kind pair and multi-digit (more than two bits) operands."""
 import numpy as np
 import pytest
 import torch
@@ -17,9 +17,10 @@ def dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
-@pytest.fixture(autouse=True)
-def force_mfma(monkeypatch):
-    monkeypatch.setenv("APNN_MFMA", "2")
+@pytest.fixture(autouse=True, params=["32", "64", "128", "256"])
+def mfma_tile(request, monkeypatch):
+    monkeypatch.delenv("APNN_MFMA", raising=False)
+    monkeypatch.setenv("APNN_MFMA_TILE", request.param)
 
 
 def gpu_gemm(W, encW, p, X, encX, q):
@@ -42,6 +43,17 @@ def test_mfma_gemm_matches_oracle(encW, p, encX, q, M, N, K):
     assert np.array_equal(gpu_gemm(W, encW, p, X, encX, q), oracle.gemm(W, encW, p, X, encX, q))
 
 
+@pytest.mark.parametrize("p,q,K", [(3, 5, 1000), (2, 8, 777), (8, 8, 250), (5, 1, 4096), (4, 4, 2048), (7, 3, 300)])
+def test_mfma_multi_digit_operands(p, q, K):
+    M, N = 150, 290
+    W = wl.uniform_codes(3 * p + K, (M, K), p)
+    X = wl.uniform_codes(5 * q + K, (N, K), q)
+    assert np.array_equal(gpu_gemm(W, U, p, X, U, q), oracle.gemm(W, U, p, X, U, q))
+    if q == 1:
+        Xs = wl.fair_signs(77, (N, K))
+        assert np.array_equal(gpu_gemm(W, U, p, Xs, P, 1), oracle.gemm(W, U, p, Xs, P, 1))
+
+
 def test_mfma_extremes():
     K = 3000
     W = np.full((260, K), 3, np.uint8)
@@ -49,6 +61,8 @@ def test_mfma_extremes():
     ones = np.ones((260, K), np.int8)
     assert (gpu_gemm(ones, P, 1, -ones, P, 1) == -K).all()
     assert (gpu_gemm(-ones, P, 1, W, U, 2) == -3 * K).all()
+    W8 = np.full((70, 255), 255, np.uint8)                 # largest 8-bit accumulators that stay exact
+    assert (gpu_gemm(W8, U, 8, W8, U, 8) == 255 * 255 * 255).all()
 
 
 def test_mfma_falls_back_when_fp32_would_not_be_exact(monkeypatch):
