@@ -20,7 +20,7 @@ OBJ = os.path.join(CSRC, "_build")
 LIB = os.path.join(HERE, "libapnn.so")
 
 SOURCES = ["common.cpp", "pack.hip", "pool.hip", "layer.hip",
-           "mfma_inst_256.hip", "mfma_inst_128.hip", "mfma_inst_64.hip", "mfma_inst_32.hip", "tile_inst_8.hip", "tile_inst_4.hip", "tile_inst_2.hip"]
+           "mfma_inst_256.hip", "mfma_inst_128.hip", "mfma_inst_64.hip", "mfma_inst_32.hip", "mfma_inst_small.hip", "mfma_inst_small_matrix.hip", "tile_inst_8.hip", "tile_inst_4.hip", "tile_inst_2.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-ffp-contract=off", "-fno-fast-math"]

@@ -85,6 +85,17 @@ static bool try_mfma(const Problem &pr, MfmaParams &mp, void *stream, int &rc)
     if (tiles > 0x7FFFFFFF) return false;
     const unsigned grid = static_cast<unsigned>(tiles);
     bool ok;
+    const char *es = std::getenv("APNN_MFMA_RESIDENT");                // 0: chunked kernel also for small layers (tests)
+    if (t == 32 && mp.Kw <= 160 && !(es && std::atoi(es) == 0)) {     // small layer, K fits on chip
+        mp.nk = 1;
+        const int nse = static_cast<int>(round_up(ceil_div(mp.Kw, 2), 16));
+        mp.c0 = (kA == OPK_PM1 && kB == OPK_PM1) ? -static_cast<int>(static_cast<int64_t>(nse) * 64 - pr.Ktotal) : 0;
+        ok = launch_mfma_small(mp, kA, kB, pr.conv, mp.Kw <= 32 ? 32 : mp.Kw <= 64 ? 64 : mp.Kw <= 96 ? 96 : 160, grid,
+                               as_stream(stream));
+        if (!ok) return false;
+        rc = check_launch(pr.who);
+        return true;
+    }
     switch (t) {
         case 256: ok = launch_mfma256(mp, kA, kB, pr.conv, grid, as_stream(stream)); break;
         case 128: ok = launch_mfma128(mp, kA, kB, pr.conv, grid, as_stream(stream)); break;

@@ -124,6 +124,43 @@ template <int N, class F> __device__ __forceinline__ void static_for(F &&f)
     }
 }
 
+// Epilogue on one output value: optional int32 store, fused scale/bias, residual,
+// floor/clamp and the ballot-packed planes.  Every lane of the wave must call it
+// (gm differs only between the two lane halves, gn = tile column base + lr).
+__device__ __forceinline__ void finish_value(const MfmaParams &p, float v, int gm, int gn, float sc, float bi,
+                                             bool have_res, uint32_t res_code, int lr, int lh)
+{
+    const bool rok = gm < p.M, cok = gn < p.N;
+    const int wcol = gn >> 5;                   // word column of this lane's channel (the 32-wide tile shares it)
+    const int y = static_cast<int>(v) + p.c0;
+    if (p.Y && rok && cok) p.Y[static_cast<int64_t>(gm) * p.N + gn] = y;
+    if (p.scale) {
+        float t = __fmaf_rn(sc, static_cast<float>(y), bi);
+        if (p.res) {
+            uint32_t code = res_code;
+            if (!have_res && rok && cok) {
+                const uint32_t *rp = p.res + static_cast<int64_t>(gm) * p.q_res * p.NW + wcol;
+                for (int b = 0; b < p.q_res; ++b) code |= ((rp[b * p.NW] >> lr) & 1u) << b;
+            }
+            t = __fmaf_rn(p.res_scale, static_cast<float>(code), t);
+        }
+        if (p.T && rok && cok) p.T[static_cast<int64_t>(gm) * p.N + gn] = t;
+        if (p.out) {
+            const float qmax = static_cast<float>((1 << p.q_out) - 1);
+            float f = floorf(t);
+            f = (f >= 0.0f) ? f : 0.0f;
+            f = (f > qmax) ? qmax : f;
+            const uint32_t code = cok ? static_cast<uint32_t>(f) : 0u;
+            uint32_t *op = p.out + static_cast<int64_t>(gm) * p.q_out * p.NW + wcol;
+            for (int b = 0; b < p.q_out; ++b) {
+                const unsigned long long bal = __ballot((code >> b) & 1u);
+                const uint32_t word = lh ? static_cast<uint32_t>(bal >> 32) : static_cast<uint32_t>(bal);
+                if (lr == 0 && rok && cok) op[b * p.NW] = word;
+            }
+        }
+    }
+}
+
 template <int KIND> struct DigitPlanes { static constexpr int value = (KIND == OPK_U2) ? 2 : 1; };
 
 template <int KA, int KB, int NWM, int NWN, int NSPLIT, int FM, int FN, int KC, int VW, bool CONV>
@@ -347,39 +384,8 @@ void mfma_fp4_kernel(const MfmaParams p)
         __syncthreads();
     }
 
-    // ---- epilogue on one output value: optional int32 store, fused scale/bias,
-    // residual, floor/clamp and the ballot-packed planes (every lane of the wave
-    // takes part; gm differs only between the two lane halves)
-    const float qmax = static_cast<float>((1 << (p.q_out > 0 ? p.q_out : 1)) - 1);
     auto finish = [&](float v, int gm, int gn, float sc, float bi, bool have_res, uint32_t res_code) {
-        const bool rok = gm < p.M, cok = gn < p.N;
-        const int wcol = gn >> 5;               // word column of this lane's channel (the 32-wide tile shares it)
-        const int y = static_cast<int>(v) + p.c0;
-        if (p.Y && rok && cok) p.Y[static_cast<int64_t>(gm) * p.N + gn] = y;
-        if (p.scale) {
-            float t = __fmaf_rn(sc, static_cast<float>(y), bi);
-            if (p.res) {
-                uint32_t code = res_code;
-                if (!have_res && rok && cok) {
-                    const uint32_t *rp = p.res + static_cast<int64_t>(gm) * p.q_res * p.NW + wcol;
-                    for (int b = 0; b < p.q_res; ++b) code |= ((rp[b * p.NW] >> lr) & 1u) << b;
-                }
-                t = __fmaf_rn(p.res_scale, static_cast<float>(code), t);
-            }
-            if (p.T && rok && cok) p.T[static_cast<int64_t>(gm) * p.N + gn] = t;
-            if (p.out) {
-                float f = floorf(t);
-                f = (f >= 0.0f) ? f : 0.0f;
-                f = (f > qmax) ? qmax : f;
-                const uint32_t code = cok ? static_cast<uint32_t>(f) : 0u;
-                uint32_t *op = p.out + static_cast<int64_t>(gm) * p.q_out * p.NW + wcol;
-                for (int b = 0; b < p.q_out; ++b) {
-                    const unsigned long long bal = __ballot((code >> b) & 1u);
-                    const uint32_t word = lh ? static_cast<uint32_t>(bal >> 32) : static_cast<uint32_t>(bal);
-                    if (lr == 0 && rok && cok) op[b * p.NW] = word;
-                }
-            }
-        }
+        finish_value(p, v, gm, gn, sc, bi, have_res, res_code, lr, lh);
     };
 
     if constexpr (NSPLIT == 1) {

@@ -14,6 +14,9 @@ bool launch_mfma64(const MfmaParams &p, int kindA, int kindB, bool conv, unsigne
 bool launch_mfma64_k8(const MfmaParams &p, int kindA, int kindB, unsigned grid, hipStream_t st);   // K <= 8 words
 bool launch_mfma32(const MfmaParams &p, int kindA, int kindB, bool conv, unsigned grid, hipStream_t st);
 
+// LDS-resident small-layer kernel: 32 x 32 tile, K <= kcmax (32, 64, 96 or 160) words per plane.
+bool launch_mfma_small(const MfmaParams &p, int kindA, int kindB, bool conv, int kcmax, unsigned grid, hipStream_t st);
+
 // K words per chunk of each tile size (must match the instances).
 constexpr int mfma_chunk_words(int tile) { return tile == 256 ? 8 : tile == 128 ? 16 : 32; }
 

@@ -17,10 +17,13 @@ def dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
-@pytest.fixture(autouse=True, params=["32", "64", "128", "256"])
+@pytest.fixture(autouse=True, params=["32", "32chunked", "64", "128", "256"])
 def mfma_tile(request, monkeypatch):
     monkeypatch.delenv("APNN_MFMA", raising=False)
-    monkeypatch.setenv("APNN_MFMA_TILE", request.param)
+    monkeypatch.delenv("APNN_MFMA_RESIDENT", raising=False)
+    monkeypatch.setenv("APNN_MFMA_TILE", request.param[:2] if request.param.startswith("32") else request.param)
+    if request.param == "32chunked":
+        monkeypatch.setenv("APNN_MFMA_RESIDENT", "0")
 
 
 def gpu_gemm(W, encW, p, X, encX, q):
