@@ -85,13 +85,17 @@ static bool try_mfma(const Problem &pr, MfmaParams &mp, void *stream, int &rc)
     if (tiles > 0x7FFFFFFF) return false;
     const unsigned grid = static_cast<unsigned>(tiles);
     bool ok;
-    const char *es = std::getenv("APNN_MFMA_RESIDENT");                // 0: chunked kernel also for small layers (tests)
-    if (t == 32 && mp.Kw <= 160 && !(es && std::atoi(es) == 0)) {     // small layer, K fits on chip
+    const char *es = std::getenv("APNN_MFMA_SMALL");                   // 0: chunked kernel also for small layers (tests)
+    if (t == 32 && !(es && std::atoi(es) == 0)) {                      // small layer: lane-private loads, no LDS staging
+        const char *en = std::getenv("APNN_MFMA_NSPLIT");
+        int nsplit = tiles <= 4096 ? 4 : 1;                            // measured: the split wins up to a few thousand tiles
+        if (en && (std::atoi(en) == 1 || std::atoi(en) == 4)) nsplit = std::atoi(en);
+        const int64_t nse = round_up(ceil_div(mp.Kw, 2), 4 * nsplit);
         mp.nk = 1;
-        const int nse = static_cast<int>(round_up(ceil_div(mp.Kw, 2), 16));
-        mp.c0 = (kA == OPK_PM1 && kB == OPK_PM1) ? -static_cast<int>(static_cast<int64_t>(nse) * 64 - pr.Ktotal) : 0;
-        ok = launch_mfma_small(mp, kA, kB, pr.conv, mp.Kw <= 32 ? 32 : mp.Kw <= 64 ? 64 : mp.Kw <= 96 ? 96 : 160, grid,
-                               as_stream(stream));
+        mp.c0 = (kA == OPK_PM1 && kB == OPK_PM1) ? -static_cast<int>(nse * 64 - pr.Ktotal) : 0;
+        const unsigned g = static_cast<unsigned>(nsplit == 1 ? ceil_div(tiles, 4) : tiles);
+        ok = pr.conv ? launch_mfma_small_conv(mp, kA, kB, mp.Cw % 4 == 0 ? 4 : 2, nsplit, g, as_stream(stream))
+                     : launch_mfma_small_matrix(mp, kA, kB, nsplit, g, as_stream(stream));
         if (!ok) return false;
         rc = check_launch(pr.who);
         return true;

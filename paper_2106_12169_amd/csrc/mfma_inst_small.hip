@@ -1,33 +1,28 @@
-// Instances of the LDS-resident small-layer matrix-core kernel (32 x 32 tile,
-// whole K on chip): K of at most 32, 64, 96 or 160 words per plane.
+// Convolution instances of the small-layer matrix-core kernel (lane-private
+// operand loads, 32 x 32 tiles): loader vector width 4 or 2 words, one tile per
+// wave or one tile per block with K split over its four waves.
 #include "mfma_launch.h"
 #include "mfma_small.h"
 
 namespace apnn {
 
-template <int KA, int KB, bool CONV> static void go(const MfmaParams &p, int kcmax, unsigned grid, hipStream_t st)
+template <int KA, int KB> static void go(const MfmaParams &p, int vw, int nsplit, unsigned grid, hipStream_t st)
 {
-    switch (kcmax) {
-        case 32: hipLaunchKernelGGL((mfma_small_kernel<KA, KB, 32, CONV>), dim3(grid), dim3(256), 0, st, p); break;
-        case 64: hipLaunchKernelGGL((mfma_small_kernel<KA, KB, 64, CONV>), dim3(grid), dim3(256), 0, st, p); break;
-        case 96: hipLaunchKernelGGL((mfma_small_kernel<KA, KB, 96, CONV>), dim3(grid), dim3(256), 0, st, p); break;
-        default: hipLaunchKernelGGL((mfma_small_kernel<KA, KB, 160, CONV>), dim3(grid), dim3(256), 0, st, p); break;
-    }
+    if (vw == 4 && nsplit == 1) hipLaunchKernelGGL((mfma_small_kernel<KA, KB, 4, true, 1>), dim3(grid), dim3(256), 0, st, p);
+    else if (vw == 4) hipLaunchKernelGGL((mfma_small_kernel<KA, KB, 4, true, 4>), dim3(grid), dim3(256), 0, st, p);
+    else if (nsplit == 1) hipLaunchKernelGGL((mfma_small_kernel<KA, KB, 2, true, 1>), dim3(grid), dim3(256), 0, st, p);
+    else hipLaunchKernelGGL((mfma_small_kernel<KA, KB, 2, true, 4>), dim3(grid), dim3(256), 0, st, p);
 }
 
-bool launch_mfma_small_matrix(const MfmaParams &p, int kindA, int kindB, int kcmax, unsigned grid, hipStream_t st);
-
-bool launch_mfma_small(const MfmaParams &p, int kindA, int kindB, bool conv, int kcmax, unsigned grid, hipStream_t st)
+bool launch_mfma_small_conv(const MfmaParams &p, int kindA, int kindB, int vw, int nsplit, unsigned grid, hipStream_t st)
 {
-    if (kcmax != 32 && kcmax != 64 && kcmax != 96 && kcmax != 160) return false;
-    if (!conv) return launch_mfma_small_matrix(p, kindA, kindB, kcmax, grid, st);
     switch (kindA * 3 + kindB) {          // features are 0/1-encoded in convolution mode
-        case 0: go<0, 0, true>(p, kcmax, grid, st); return true;
-        case 1: go<0, 1, true>(p, kcmax, grid, st); return true;
-        case 2: go<0, 2, true>(p, kcmax, grid, st); return true;
-        case 3: go<1, 0, true>(p, kcmax, grid, st); return true;
-        case 4: go<1, 1, true>(p, kcmax, grid, st); return true;
-        case 5: go<1, 2, true>(p, kcmax, grid, st); return true;
+        case 0: go<0, 0>(p, vw, nsplit, grid, st); return true;
+        case 1: go<0, 1>(p, vw, nsplit, grid, st); return true;
+        case 2: go<0, 2>(p, vw, nsplit, grid, st); return true;
+        case 3: go<1, 0>(p, vw, nsplit, grid, st); return true;
+        case 4: go<1, 1>(p, vw, nsplit, grid, st); return true;
+        case 5: go<1, 2>(p, vw, nsplit, grid, st); return true;
         default: return false;
     }
 }

@@ -14,8 +14,11 @@ bool launch_mfma64(const MfmaParams &p, int kindA, int kindB, bool conv, unsigne
 bool launch_mfma64_k8(const MfmaParams &p, int kindA, int kindB, unsigned grid, hipStream_t st);   // K <= 8 words
 bool launch_mfma32(const MfmaParams &p, int kindA, int kindB, bool conv, unsigned grid, hipStream_t st);
 
-// LDS-resident small-layer kernel: 32 x 32 tile, K <= kcmax (32, 64, 96 or 160) words per plane.
-bool launch_mfma_small(const MfmaParams &p, int kindA, int kindB, bool conv, int kcmax, unsigned grid, hipStream_t st);
+// Small-layer kernel (lane-private operand loads, 32 x 32 tiles); nsplit = 1: one
+// tile per wave (grid = ceil(tiles / 4)), nsplit = 4: one tile per block, K split
+// over its waves (grid = tiles).  vw: conv loader vector width in words (4 or 2).
+bool launch_mfma_small_conv(const MfmaParams &p, int kindA, int kindB, int vw, int nsplit, unsigned grid, hipStream_t st);
+bool launch_mfma_small_matrix(const MfmaParams &p, int kindA, int kindB, int nsplit, unsigned grid, hipStream_t st);
 
 // K words per chunk of each tile size (must match the instances).
 constexpr int mfma_chunk_words(int tile) { return tile == 256 ? 8 : tile == 128 ? 16 : 32; }

@@ -1,145 +1,134 @@
-// Matrix-core kernel for small layers: the whole K extent of a 32 x 32 output
-// tile is resident in LDS.
+// Matrix-core kernel for small layers: no LDS staging, every lane loads its own
+// operand words.
 //
-// Late network layers have few output pixels and a K that fits on chip (at
-// most KCMAX words per plane), so they are bound by latency, not throughput: a
-// chunked loop would pay one exposed memory round trip per chunk.  Here every
-// thread issues all of its global loads at once, the block synchronises once
-// per digit pair, and the four waves split the matrix-instruction steps of the
-// tile between them (partial tiles added through LDS, epilogue rows shared out
-// as in the K-split mode of the chunked kernel).  Arithmetic, operand encodings
-// and epilogue are those of mfma_fp4_kernel.
+// Late network layers have few output pixels, so a launch runs about one wave
+// per SIMD and its duration is the length of the instruction stream of a wave.
+// A cooperative global -> register -> LDS -> register pipeline costs more
+// instructions than the arithmetic itself, so here lane (half lh, row lr) of a
+// wave reads, straight from global memory, the 16-byte pieces of its own tile
+// row that its matrix-instruction steps consume: piece (row lr, words 4i..4i+3)
+// is needed by exactly one lane of the block, nothing is loaded twice and there
+// is no barrier before the arithmetic.  All loads of up to GMAX groups of four
+// steps are issued before the first of them is used.  With NSPLIT = 4 the four
+// waves of a block share one 32 x 32 tile and split its steps (layers with a long
+// K and few tiles); with NSPLIT = 1 every wave owns its own tile (layers with a
+// short K and many tiles).  Arithmetic, operand encodings, digit passes and the
+// epilogue are those of mfma_fp4_kernel.
 //
-// Step geometry (run time): nsteps = ceil(Kw / 2) steps would do; it is rounded
-// up to NSe, a multiple of 16, so that every wave owns whole groups of four
-// steps.  Lane-half h of step s takes word h*NSe + s of the LDS row (any
-// pairing of K positions with steps is valid as long as both operands use the
-// same one); words at and beyond Kw are zero.
+// Step geometry (run time): ceil(Kw / 2) steps would do; that is rounded up to
+// NSe, a multiple of 4 * NSPLIT, so that every wave owns whole groups of four
+// steps.  Lane-half h of step s takes K word h*NSe + s (any pairing of K
+// positions with steps is valid as long as both operands use the same one);
+// words at and beyond Kw read as zero.
 #pragma once
 #include "mfma_kernel.h"
 
 namespace apnn {
 
-template <int KA, int KB, int KCMAX, bool CONV>
-__global__ __launch_bounds__(256, 2) void mfma_small_kernel(const MfmaParams p)
+template <int KA, int KB, int VW, bool CONV, int NSPLIT>
+__global__ __launch_bounds__(256) void mfma_small_kernel(const MfmaParams p)
 {
-    static_assert(KCMAX % 32 == 0, "LDS rows hold two halves of a multiple of 16 steps");
+    constexpr int GMAX = 5;                             // groups of four steps whose loads are in flight together
     constexpr int LA = DigitPlanes<KA>::value, LB = DigitPlanes<KB>::value;
-    constexpr int VWA = CONV ? 2 : 4, VWB = CONV ? 2 : 4;         // loader vector widths (conv rows are 8-byte aligned)
-    constexpr int RSA = LA * KCMAX + 4, RSB = LB * KCMAX + 4;     // padded LDS row strides (words)
-    constexpr int A_SLOTS = LA * KCMAX / VWA / 8, B_SLOTS = LB * KCMAX / VWB / 8;   // pieces per thread (8 threads per row)
-    constexpr int TILE_WORDS = 32 * RSA + 32 * RSB, RED_WORDS = 4 * 16 * 64;
-    using VecA = typename VecT<VWA>::type;
-    using VecB = typename VecT<VWB>::type;
+    constexpr int RPW = 16 / NSPLIT;                    // accumulator registers a wave finishes in the epilogue
 
-    __shared__ __attribute__((aligned(16))) uint32_t smem[TILE_WORDS > RED_WORDS ? TILE_WORDS : RED_WORDS];
-    uint32_t *sA = smem, *sB = smem + 32 * RSA;
+    __shared__ float sRed[NSPLIT > 1 ? NSPLIT : 1][NSPLIT > 1 ? 16 : 1][64];
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, ks = tid >> 6;           // wave = K-split index
+    const int lane = tid & 63, wave = tid >> 6;
     const int lr = lane & 31, lh = lane >> 5;
+    const int ks = NSPLIT > 1 ? wave : 0;               // K-split index of this wave
 
-    const int tilesN = (p.N + 31) / 32;
-    const int m0 = (blockIdx.x / tilesN) * 32, n0 = (blockIdx.x % tilesN) * 32;
+    // tile of this wave: with NSPLIT = 1 the block covers four consecutive tiles of the row-major tile grid
+    const int tilesN = (p.N + 31) / 32, tilesM = (p.M + 31) / 32;
+    const int tile = NSPLIT > 1 ? blockIdx.x : blockIdx.x * 4 + wave;
+    const bool live = tile < tilesM * tilesN;           // trailing waves of the last block have no tile
+    const int m0 = (tile / tilesN) * 32, n0 = (tile % tilesN) * 32;
 
-    const int NSe = (((p.Kw + 1) >> 1) + 15) & ~15;     // steps per digit pair, multiple of 16
-    const int G = NSe >> 4;                             // groups of four steps per wave
-    const int row_words = 2 * NSe;                      // LDS words per (row, plane) that the steps read
+    const int NSe = (((p.Kw + 1) >> 1) + 4 * NSPLIT - 1) / (4 * NSPLIT) * (4 * NSPLIT);
+    const int G = NSe / (4 * NSPLIT);                   // groups of four steps of this wave
 
     Fp4Masks km;
     km.m1 = reg_const(0x11111111u); km.m2 = reg_const(0x22222222u);
     km.m4 = reg_const(0x44444444u); km.m8 = reg_const(0x88888888u);
 
-    // ---- loader.  Eight consecutive threads share a tile row and read consecutive
-    // pieces of it, so a wave touches few cache lines per load instruction; a
-    // thread keeps its row (one set of pixel coordinates) for all of its loads.
-    // The planes of one digit are adjacent in memory (fmap: [pixel][plane][Cw],
-    // matrix: [row][plane][ldw]), so piece j of a row is tap j / PPT and word
-    // (j % PPT) * VW of that tap's run of LA * RUN words.
-    const int lrow = tid >> 3, lsub = tid & 7;
-    const int runA = CONV ? p.Cw : p.ldwA, runB = p.ldwB;           // words per plane of one contiguous run
-    const int pptA = LA * runA / VWA, pptB = LB * runB / VWB;       // pieces per run
-    const float inv_pptA = 1.0f / static_cast<float>(pptA), inv_runA = 1.0f / static_cast<float>(runA);
-    const float inv_runB = 1.0f / static_cast<float>(runB);
-    const int piecesA = LA * p.Kw / VWA, piecesB = LB * p.Kw / VWB;  // pieces per tile row that carry data
-    int a_h0 = 0, a_w0 = 0, a_pix = 0;
+    // this lane's operand rows
+    const int gmA = m0 + lr, gnB = n0 + lr;
+    const bool a_ok = live && gmA < p.M, b_ok = live && gnB < p.N;
+    int a_h0 = 0, a_w0 = 0;
+    int64_t a_pix = 0;
     if (CONV) {
-        const int gm = m0 + lrow;
-        const int wo = gm % p.Wo, ho = (gm / p.Wo) % p.Ho, n = gm / (p.Wo * p.Ho);
+        const int wo = gmA % p.Wo, ho = (gmA / p.Wo) % p.Ho, n = gmA / (p.Wo * p.Ho);
         a_h0 = ho * p.stride - p.pad;
         a_w0 = wo * p.stride - p.pad;
-        a_pix = n * p.H * p.W;
+        a_pix = static_cast<int64_t>(n) * p.H * p.W;
     }
-    VecA ra[A_SLOTS];
-    VecB rb[B_SLOTS];
-    int la[A_SLOTS], lb[B_SLOTS];                       // LDS word offsets of the pieces (or -1)
-    auto fetch = [&](int da, int db) {
-        const int gm = m0 + lrow, gn = n0 + lrow;
+    const uint32_t *b_row = p.B + static_cast<int64_t>(gnB) * p.PB * p.ldwB;
+    const uint32_t *a_row = p.A + static_cast<int64_t>(gmA) * p.PA * p.ldwA;      // matrix mode
+
+    // Words kk .. kk+3 of plane `plane` of this lane's A row (zero beyond Kw / outside the frame).
+    auto load_a = [&](int plane, int kk) -> uint4 {
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (!a_ok || kk >= p.Kw || plane >= p.PA) return v;
+        if (CONV) {
+            // VW = 4: the four words lie in one tap; VW = 2: two taps of two words each
 #pragma unroll
-        for (int u = 0; u < A_SLOTS; ++u) {
-            const int j = 8 * u + lsub;
-            ra[u] = vec_zero<VWA>();
-            la[u] = -1;
-            if (j < piecesA) {
-                const int tap = static_cast<int>((static_cast<float>(j) + 0.5f) * inv_pptA);
-                const int off = (j - tap * pptA) * VWA;                         // word inside the run of LA planes
-                const int pl = static_cast<int>((static_cast<float>(off) + 0.5f) * inv_runA);
-                const int cw = off - pl * runA;
-                const int plane = (LA == 2 ? 2 * da : da) + pl;
-                la[u] = lrow * RSA + pl * KCMAX + tap * runA + cw;
-                if (gm < p.M && plane < p.PA) {
-                    if (CONV) {
-                        const int r = tap / p.S, sc = tap - r * p.S;
-                        const int h = a_h0 + r, w = a_w0 + sc;
-                        if (h >= 0 && h < p.H && w >= 0 && w < p.W) {
-                            const int64_t pix = a_pix + h * p.W + w;
-                            ra[u] = *reinterpret_cast<const VecA *>(p.A + (pix * p.PA + plane) * p.Cw + cw);
+            for (int part = 0; part < 4 / VW; ++part) {
+                const int k = kk + part * VW;
+                if (k < p.Kw) {
+                    const int tap = static_cast<int>((static_cast<float>(k) + 0.5f) * p.invCw);
+                    const int cw = k - tap * p.Cw;
+                    const int r = tap / p.S, sc = tap - r * p.S;
+                    const int h = a_h0 + r, w = a_w0 + sc;
+                    if (h >= 0 && h < p.H && w >= 0 && w < p.W) {
+                        const uint32_t *src = p.A + ((a_pix + h * p.W + w) * p.PA + plane) * p.Cw + cw;
+                        if (VW == 4) {
+                            v = *reinterpret_cast<const uint4 *>(src);
+                        } else {
+                            const uint2 t = *reinterpret_cast<const uint2 *>(src);
+                            if (part == 0) { v.x = t.x; v.y = t.y; } else { v.z = t.x; v.w = t.y; }
                         }
-                    } else {
-                        ra[u] = *reinterpret_cast<const VecA *>(p.A + (static_cast<int64_t>(gm) * p.PA + plane) * p.ldwA + cw);
                     }
                 }
             }
+        } else {
+            v = *reinterpret_cast<const uint4 *>(a_row + static_cast<int64_t>(plane) * p.ldwA + kk);
         }
-#pragma unroll
-        for (int u = 0; u < B_SLOTS; ++u) {
-            const int j = 8 * u + lsub;
-            rb[u] = vec_zero<VWB>();
-            lb[u] = -1;
-            if (j < piecesB) {
-                const int off = j * VWB;
-                const int pl = static_cast<int>((static_cast<float>(off) + 0.5f) * inv_runB);
-                const int cw = off - pl * runB;
-                const int plane = (LB == 2 ? 2 * db : db) + pl;
-                lb[u] = lrow * RSB + pl * KCMAX + cw;
-                if (gn < p.N && plane < p.PB)
-                    rb[u] = *reinterpret_cast<const VecB *>(p.B + (static_cast<int64_t>(gn) * p.PB + plane) * p.ldwB + cw);
+        return v;
+    };
+    auto load_b = [&](int plane, int kk) -> uint4 {
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (!b_ok || kk >= p.Kw || plane >= p.PB) return v;
+        const uint32_t *src = b_row + static_cast<int64_t>(plane) * p.ldwB + kk;
+        if (!CONV) {
+            v = *reinterpret_cast<const uint4 *>(src);
+        } else {                                // conv weight rows are 8-byte aligned and an even number of words long
+            const uint2 lo = *reinterpret_cast<const uint2 *>(src);
+            v.x = lo.x; v.y = lo.y;
+            if (kk + 4 <= p.Kw) {
+                const uint2 hi = *reinterpret_cast<const uint2 *>(src + 2);
+                v.z = hi.x; v.w = hi.y;
             }
         }
+        return v;
     };
-    // LDS words [Kw, row_words) of every (row, plane) must read as zero: they are
-    // cleared once (from the last 16-byte boundary below Kw; the data pieces are
-    // written after the barrier and rewritten per digit pair)
-    {
-        const int kz = p.Kw & ~3, nz = (row_words - kz) >> 2;       // uint4 vectors to clear per (row, plane)
-        for (int i = tid; i < 32 * LA * nz; i += 256) {
-            const int rp = i / nz, c = i - rp * nz;
-            *reinterpret_cast<uint4 *>(&sA[(rp / LA) * RSA + (rp % LA) * KCMAX + kz + 4 * c]) = make_uint4(0, 0, 0, 0);
+
+    // the epilogue's per-channel parameters and residual codes: their latency hides behind the main loop
+    const int gn = n0 + lr;
+    float sc = 0.0f, bi = 0.0f;
+    if (p.scale && live && gn < p.N) { sc = p.scale[gn]; bi = p.bias[gn]; }
+    uint32_t pre_res[RPW];
+#pragma unroll
+    for (int rr = 0; rr < RPW; ++rr) {
+        const int r = ks * RPW + rr;
+        const int gm = m0 + 8 * (r >> 2) + 4 * lh + (r & 3);
+        uint32_t code = 0;
+        if (p.res && live && gm < p.M && gn < p.N) {
+            const uint32_t *rp = p.res + static_cast<int64_t>(gm) * p.q_res * p.NW + (gn >> 5);
+            for (int b = 0; b < p.q_res; ++b) code |= ((rp[b * p.NW] >> lr) & 1u) << b;
         }
-        for (int i = tid; i < 32 * LB * nz; i += 256) {
-            const int rp = i / nz, c = i - rp * nz;
-            *reinterpret_cast<uint4 *>(&sB[(rp / LB) * RSB + (rp % LB) * KCMAX + kz + 4 * c]) = make_uint4(0, 0, 0, 0);
-        }
+        pre_res[rr] = code;
     }
-    __syncthreads();
-    auto stage = [&]() {
-#pragma unroll
-        for (int u = 0; u < A_SLOTS; ++u)
-            if (la[u] >= 0) *reinterpret_cast<VecA *>(&sA[la[u]]) = ra[u];
-#pragma unroll
-        for (int u = 0; u < B_SLOTS; ++u)
-            if (lb[u] >= 0) *reinterpret_cast<VecB *>(&sB[lb[u]]) = rb[u];
-    };
 
     // digit pairs diagonal by diagonal, Horner evaluation in base 4 (as in mfma_fp4_kernel)
     const int dmax = p.DA + p.DB - 2;
@@ -153,73 +142,68 @@ __global__ __launch_bounds__(256, 2) void mfma_small_kernel(const MfmaParams p)
     };
     const int npairs = p.Kw > 0 ? p.DA * p.DB : 0;
     int da = first_a(dmax), db = dmax - da;
-    if (npairs > 0) fetch(da, db);
-
-    // the epilogue's per-channel parameters and residual codes: their latency hides behind the loads above
-    const int gn = n0 + lr;
-    float sc = 0.0f, bi = 0.0f;
-    if (p.scale && gn < p.N) { sc = p.scale[gn]; bi = p.bias[gn]; }
-    uint32_t pre_res[4];
-#pragma unroll
-    for (int rr = 0; rr < 4; ++rr) {
-        const int gm = m0 + 8 * ks + 4 * lh + rr;       // accumulator register 4 ks + rr
-        uint32_t code = 0;
-        if (p.res && gm < p.M && gn < p.N) {
-            const uint32_t *rp = p.res + static_cast<int64_t>(gm) * p.q_res * p.NW + (gn >> 5);
-            for (int b = 0; b < p.q_res; ++b) code |= ((rp[b * p.NW] >> lr) & 1u) << b;
-        }
-        pre_res[rr] = code;
-    }
 
     v16f_t acc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
 
     for (int pair = 0; pair < npairs; ++pair) {
-        stage();
-        __syncthreads();
-        int na = da, nb = db;
-        const bool new_diag = next_pair(na, nb);
-        if (pair + 1 < npairs) fetch(na, nb);           // next pair's loads fly during this pair's steps
-
-        const uint32_t *pa = &sA[lr * RSA + lh * NSe + ks * G * 4];
-        const uint32_t *pb = &sB[lr * RSB + lh * NSe + ks * G * 4];
-        for (int g = 0; g < G; ++g) {
-            uint4 wa[LA], wb[LB];
+        const int planeA = LA == 2 ? 2 * da : da, planeB = LB == 2 ? 2 * db : db;
+        const int kbase = lh * NSe + ks * G * 4;        // first K word of this lane's steps
+        for (int g0 = 0; g0 < G; g0 += GMAX) {
+            uint4 wa[GMAX][LA], wb[GMAX][LB];
 #pragma unroll
-            for (int pl = 0; pl < LA; ++pl) wa[pl] = *reinterpret_cast<const uint4 *>(pa + pl * KCMAX + 4 * g);
+            for (int g = 0; g < GMAX; ++g) {
+                const int kk = (g0 + g < G) ? kbase + 4 * (g0 + g) : p.Kw;       // beyond G: reads as zero, not used
 #pragma unroll
-            for (int pl = 0; pl < LB; ++pl) wb[pl] = *reinterpret_cast<const uint4 *>(pb + pl * KCMAX + 4 * g);
-            const uint32_t a0[4] = {wa[0].x, wa[0].y, wa[0].z, wa[0].w};
-            const uint32_t a1[4] = {wa[LA - 1].x, wa[LA - 1].y, wa[LA - 1].z, wa[LA - 1].w};
-            const uint32_t b0[4] = {wb[0].x, wb[0].y, wb[0].z, wb[0].w};
-            const uint32_t b1[4] = {wb[LB - 1].x, wb[LB - 1].y, wb[LB - 1].z, wb[LB - 1].w};
+                for (int pl = 0; pl < LA; ++pl) wa[g][pl] = load_a(planeA + pl, kk);
 #pragma unroll
-            for (int st = 0; st < 4; ++st) {
-                v8i_t fa, fb;
-                expand_fp4<KA>(a0[st], a1[st], km, fa);
-                expand_fp4<KB>(b0[st], b1[st], km, fb);
-                acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fa, fb, acc, 4, 4, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
+                for (int pl = 0; pl < LB; ++pl) wb[g][pl] = load_b(planeB + pl, kk);
+            }
+#pragma unroll
+            for (int g = 0; g < GMAX; ++g) {
+                if (g0 + g < G) {
+                    const uint32_t a0[4] = {wa[g][0].x, wa[g][0].y, wa[g][0].z, wa[g][0].w};
+                    const uint32_t a1[4] = {wa[g][LA - 1].x, wa[g][LA - 1].y, wa[g][LA - 1].z, wa[g][LA - 1].w};
+                    const uint32_t b0[4] = {wb[g][0].x, wb[g][0].y, wb[g][0].z, wb[g][0].w};
+                    const uint32_t b1[4] = {wb[g][LB - 1].x, wb[g][LB - 1].y, wb[g][LB - 1].z, wb[g][LB - 1].w};
+#pragma unroll
+                    for (int st = 0; st < 4; ++st) {
+                        v8i_t fa, fb;
+                        expand_fp4<KA>(a0[st], a1[st], km, fa);
+                        expand_fp4<KB>(b0[st], b1[st], km, fb);
+                        acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fa, fb, acc, 4, 4, 0, 0x7f7f7f7f, 0,
+                                                                               0x7f7f7f7f);
+                    }
+                }
             }
         }
+        const bool new_diag = next_pair(da, db);
         if (new_diag && pair + 1 < npairs) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[r] *= 4.0f;
         }
-        da = na; db = nb;
-        __syncthreads();                                // all waves are done with the tile before it is overwritten
     }
 
-    // ---- add the four partial tiles; wave ks finishes accumulator registers 4 ks .. 4 ks + 3
-    float (*sRed)[16][64] = reinterpret_cast<float (*)[16][64]>(smem);
+    if constexpr (NSPLIT == 1) {
+        if (!live) return;                      // wave-uniform: the ballots below stay whole-wave
+        static_for<16>([&](auto rc) {
+            constexpr int r = decltype(rc)::value;
+            finish_value(p, acc[r], m0 + 8 * (r >> 2) + 4 * lh + (r & 3), gn, sc, bi, true, pre_res[r], lr, lh);
+        });
+    } else {
+        // add the partial tiles; wave ks finishes accumulator registers RPW ks .. RPW ks + RPW - 1
 #pragma unroll
-    for (int r = 0; r < 16; ++r) sRed[ks][r][lane] = acc[r];
-    __syncthreads();
+        for (int r = 0; r < 16; ++r) sRed[ks][r][lane] = acc[r];
+        __syncthreads();
 #pragma unroll
-    for (int rr = 0; rr < 4; ++rr) {
-        const int r = 4 * ks + rr;
-        const float v = sRed[0][r][lane] + sRed[1][r][lane] + sRed[2][r][lane] + sRed[3][r][lane];
-        finish_value(p, v, m0 + 8 * ks + 4 * lh + rr, gn, sc, bi, true, pre_res[rr], lr, lh);
+        for (int rr = 0; rr < RPW; ++rr) {
+            const int r = ks * RPW + rr;
+            float v = 0.0f;
+#pragma unroll
+            for (int k = 0; k < NSPLIT; ++k) v += sRed[k][r][lane];
+            finish_value(p, v, m0 + 8 * (r >> 2) + 4 * lh + (r & 3), gn, sc, bi, true, pre_res[rr], lr, lh);
+        }
     }
 }
 

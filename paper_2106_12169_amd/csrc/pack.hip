@@ -120,41 +120,51 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(const float *__restr
 }
 
 // Input-layer receptive-field packing: word r of an output pixel holds bit
-// (s*C + c) = bit t of image[n][c][ho*stride+r-pad][wo*stride+s-pad].  The S*C
-// bytes of one kernel row are first collected four to a register; every plane
-// then takes one bit of each byte with the same gather as the row packer.
+// (s*C + c) = bit t of image[n][c][ho*stride+r-pad][wo*stride+s-pad].  A block
+// handles 32 output pixels; thread (pixel, r) collects the S*C bytes of kernel row
+// r four to a register, every plane takes one bit of each byte with the same
+// gather as the row packer, and the 32 x bits x ldw words of the block, which are
+// contiguous in the destination, leave through LDS as coalesced 16-byte stores.
 __global__ __launch_bounds__(256) void pack_patches_kernel(const uint8_t *__restrict__ img,
                                                            uint32_t *__restrict__ dst, int64_t npix,
                                                            int C, int H, int W, int Ho, int Wo, int R, int S,
-                                                           int stride, int pad, int bits, int ldw)
+                                                           int stride, int pad, int bits, int LDW)
 {
-    const int64_t idx = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
-    if (idx >= npix * ldw) return;
-    const int64_t pix = idx / ldw;
-    const int r = static_cast<int>(idx - pix * ldw);
-    const int wo = static_cast<int>(pix % Wo);
-    const int ho = static_cast<int>((pix / Wo) % Ho);
-    const int64_t n = pix / (static_cast<int64_t>(Wo) * Ho);
-    uint32_t d[8] = {0, 0, 0, 0, 0, 0, 0, 0};        // byte (s*C + c) of the kernel row, 4 per register
-    const int h = ho * stride + r - pad;
-    if (r < R && h >= 0 && h < H) {
-        const int x0 = wo * stride - pad;
+    // LDW = words per plane row, 4 or 8 (host checks R <= 8)
+    __shared__ __attribute__((aligned(16))) uint32_t tile[32 * 8 * 8];
+    const int tid = threadIdx.x;
+    const int r = tid & 7, lp = tid >> 3;                // kernel row, pixel inside the block
+    const int64_t pix = static_cast<int64_t>(blockIdx.x) * 32 + lp;
+    uint32_t d[8] = {0, 0, 0, 0, 0, 0, 0, 0};            // byte (s*C + c) of the kernel row, 4 per register
+    if (pix < npix) {
+        const int wo = static_cast<int>(pix % Wo);
+        const int ho = static_cast<int>((pix / Wo) % Ho);
+        const int64_t n = pix / (static_cast<int64_t>(Wo) * Ho);
+        const int h = ho * stride + r - pad;
+        if (r < R && h >= 0 && h < H) {
+            const int x0 = wo * stride - pad;
+            int sc = 0, c = 0;                               // i = sc*C + c, stepped without dividing
 #pragma unroll
-        for (int i = 0; i < 32; ++i) {
-            const int sc = i / C, c = i - sc * C, x = x0 + sc;   // C is small: the division is cheap integer work
-            if (i < S * C && x >= 0 && x < W)
-                d[i >> 2] |= static_cast<uint32_t>(img[((n * C + c) * H + h) * W + x]) << (8 * (i & 3));
+            for (int i = 0; i < 32; ++i) {
+                const int x = x0 + sc;
+                if (i < S * C && x >= 0 && x < W)
+                    d[i >> 2] |= static_cast<uint32_t>(img[((n * C + c) * H + h) * W + x]) << (8 * (i & 3));
+                if (++c == C) { c = 0; ++sc; }
+            }
         }
     }
+    for (int t = 0; t < bits; ++t) {
+        uint32_t w = 0;
 #pragma unroll
-    for (int t = 0; t < 8; ++t) {
-        if (t < bits) {
-            uint32_t w = 0;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) w |= gather4((d[i] >> t) & 0x01010101u) << (4 * i);
-            dst[(static_cast<size_t>(pix) * bits + t) * ldw + r] = w;
-        }
+        for (int i = 0; i < 8; ++i) w |= gather4((d[i] >> t) & 0x01010101u) << (4 * i);
+        if (r < LDW) tile[(lp * bits + t) * LDW + r] = w;
     }
+    __syncthreads();
+    const int64_t base = static_cast<int64_t>(blockIdx.x) * 32 * bits * LDW;      // words
+    const int64_t limit = npix * bits * LDW;
+    for (int v = tid; v < 32 * bits * LDW / 4; v += 256)
+        if (base + 4 * v < limit)
+            *reinterpret_cast<uint4 *>(dst + base + 4 * v) = *reinterpret_cast<const uint4 *>(&tile[4 * v]);
 }
 
 __global__ __launch_bounds__(256) void pack_patch_weights_kernel(const uint8_t *__restrict__ wsrc,
@@ -268,9 +278,10 @@ extern "C" int apnn_pack_patches(const uint8_t *src_dev, int64_t N, int64_t C, i
     if (!src_dev || !dst_dev) return fail(APNN_ERR_INVALID_ARG, "apnn_pack_patches: null pointer");
     if (!aligned16(dst_dev)) return fail(APNN_ERR_ALIGNMENT, "apnn_pack_patches: dst_dev not 16-byte aligned");
     const int Ho = static_cast<int>((H + 2 * pad - R) / stride + 1), Wo = static_cast<int>((W + 2 * pad - S) / stride + 1);
+    if (R > 8) return fail(APNN_ERR_UNSUPPORTED, "apnn_pack_patches: kernel height %d above 8", R);
     const int ldw = static_cast<int>(apnn_row_words(32 * static_cast<int64_t>(R)));
     const int64_t npix = N * Ho * Wo;
-    const unsigned grid = static_cast<unsigned>(ceil_div(npix * ldw, 256));
+    const unsigned grid = static_cast<unsigned>(ceil_div(npix, 32));
     hipLaunchKernelGGL(pack_patches_kernel, dim3(grid), dim3(256), 0, as_stream(stream), src_dev, dst_dev, npix,
                        static_cast<int>(C), static_cast<int>(H), static_cast<int>(W), Ho, Wo, R, S, stride, pad, bits, ldw);
     return check_launch("apnn_pack_patches");

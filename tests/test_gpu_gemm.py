@@ -26,19 +26,22 @@ def gpu_gemm(W, encW, p, X, encX, q):
     return Y.cpu().numpy()
 
 
-@pytest.fixture(params=["auto", "pop8", "pop4", "pop2", "mfma32", "mfma32chunked", "mfma64", "mfma128", "mfma256"])
+@pytest.fixture(params=["auto", "pop8", "pop4", "pop2", "mfma32", "mfma32split1", "mfma32split4", "mfma32chunked", "mfma64", "mfma128", "mfma256"])
 def tile(request, monkeypatch):
     """Kernel path under test: the library's own choice, the AND+popcount kernel with
     each register tile, or the FP4 matrix-core kernel with each block tile."""
-    for v in ("APNN_TILE", "APNN_MFMA", "APNN_MFMA_TILE", "APNN_MFMA_RESIDENT"):
+    for v in ("APNN_TILE", "APNN_MFMA", "APNN_MFMA_TILE", "APNN_MFMA_SMALL", "APNN_MFMA_NSPLIT"):
         monkeypatch.delenv(v, raising=False)
     kind = request.param
     if kind.startswith("pop"):
         monkeypatch.setenv("APNN_MFMA", "0")
         monkeypatch.setenv("APNN_TILE", kind[3:])
+    elif kind.startswith("mfma32split"):                # lane-private small-layer kernel, forced K split
+        monkeypatch.setenv("APNN_MFMA_TILE", "32")
+        monkeypatch.setenv("APNN_MFMA_NSPLIT", kind[-1])
     elif kind == "mfma32chunked":                      # K-split tile with the chunked loop instead of the resident one
         monkeypatch.setenv("APNN_MFMA_TILE", "32")
-        monkeypatch.setenv("APNN_MFMA_RESIDENT", "0")
+        monkeypatch.setenv("APNN_MFMA_SMALL", "0")
     elif kind.startswith("mfma"):
         monkeypatch.setenv("APNN_MFMA_TILE", kind[4:])
     return kind

@@ -17,13 +17,16 @@ def dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
-@pytest.fixture(autouse=True, params=["32", "32chunked", "64", "128", "256"])
+@pytest.fixture(autouse=True, params=["32", "32split1", "32split4", "32chunked", "64", "128", "256"])
 def mfma_tile(request, monkeypatch):
     monkeypatch.delenv("APNN_MFMA", raising=False)
-    monkeypatch.delenv("APNN_MFMA_RESIDENT", raising=False)
+    monkeypatch.delenv("APNN_MFMA_SMALL", raising=False)
     monkeypatch.setenv("APNN_MFMA_TILE", request.param[:2] if request.param.startswith("32") else request.param)
+    monkeypatch.delenv("APNN_MFMA_NSPLIT", raising=False)
     if request.param == "32chunked":
-        monkeypatch.setenv("APNN_MFMA_RESIDENT", "0")
+        monkeypatch.setenv("APNN_MFMA_SMALL", "0")
+    if request.param.startswith("32split"):
+        monkeypatch.setenv("APNN_MFMA_NSPLIT", request.param[-1])
 
 
 def gpu_gemm(W, encW, p, X, encX, q):
