@@ -189,9 +189,10 @@ def extra_configs(B, wl, dev, graph_time):
         Xp = B.apnn_pack(dev(wk.activations()), wk.q, wk.encX)
         Y = torch.empty((wk.M, wk.N), dtype=torch.int32, device="cuda")
         t = graph_time(lambda: B.apnn_gemm(Wp, Xp, wk.M, wk.N, wk.K, wk.p, wk.q, wk.encW, wk.encX, out=Y))
-        lane = 2.0 * wk.M * wk.N * wk.K * wk.p * wk.q / 32.0
+        # the FP4 matrix-core kernel runs ceil(p/2)*ceil(q/2) base-4 digit passes of 2*M*N*K flops each
+        passes = ((wk.p + 1) // 2) * ((wk.q + 1) // 2)
         return {"us": round(t * 1e6, 2), "eff_tops": round(wk.effective_ops / t / 1e12, 2),
-                "valu_frac": round(lane / t / VALU_PEAK_LANE_OPS, 4)}
+                "digit_passes": passes, "fp4_mfma_frac": round(wk.effective_ops * passes / t / MFMA_FP4_PEAK, 4)}
 
     ex["config0_gemm_w1a2_128"] = gemm_case(wl.CONFIG0)
     ex["config2_sweep_2048"] = {f"w{wk.p}a{wk.q}": gemm_case(wk) for wk in wl.CONFIG2}
@@ -203,10 +204,9 @@ def extra_configs(B, wl, dev, graph_time):
     sc, bi = dev(c.scale()), dev(c.bias())
     outp = torch.empty(B.apnn_fmap_words(d.N * d.Ho * d.Wo, c.Cout, c.q_out), dtype=torch.int32, device="cuda")
     t = graph_time(lambda: B.apnn_layer(d, Wp, Xp, q_out=c.q_out, scale=sc, bias=bi, out=outp))
-    lane = c.effective_ops * c.p * c.q / 32.0
     ex["config3_conv_layer"] = {"us": round(t * 1e6, 2), "eff_tops": round(c.effective_ops / t / 1e12, 2),
-                                "valu_frac": round(lane / t / VALU_PEAK_LANE_OPS, 4),
-                                "what": "fused conv + scale/bias + requantise + repack, packed in/out"}
+                                "fp4_mfma_frac": round(c.effective_ops / t / MFMA_FP4_PEAK, 4),
+                                "what": "fused conv + scale/bias + requantise + repack, packed in/out (latency bound)"}
 
     layers = wl.resnet18_layers()
     net = PackedNet(layers, wl.network_params(layers), 8)

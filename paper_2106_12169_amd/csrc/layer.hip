@@ -74,6 +74,7 @@ static bool try_mfma(const Problem &pr, MfmaParams &mp, void *stream, int &rc)
     if (pr.Ktotal <= 0 || round_up(pr.Ktotal, 1024) * maxA * maxB >= (int64_t(1) << 24)) return false;
     if (pr.conv && (kA == OPK_PM1 || mp.Cw % 2 != 0)) return false;
     mp.PA = pr.PA; mp.PB = pr.PB;
+    mp.out_scale = (kA == OPK_U2 ? 2.0f : 1.0f) * (kB == OPK_U2 ? 2.0f : 1.0f);
     // 0 pad bits of two -1/+1 operands multiply to +1 at every padded K position
     int t = pick_mfma_tile(pr.M, pr.N, pr.conv);
     const bool short_k = !pr.conv && mp.Kw <= 8 && t <= 64;      // 8-word chunks: no step multiplies padding

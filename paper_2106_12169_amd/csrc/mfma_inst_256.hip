@@ -5,7 +5,7 @@ namespace apnn {
 
 template <int KA, int KB, bool CONV> static void go(const MfmaParams &p, unsigned grid, hipStream_t st)
 {
-    hipLaunchKernelGGL((mfma_fp4_kernel<KA, KB, 2, 4, 1, 4, 2, 8, (CONV ? 2 : 4), CONV>), dim3(grid), dim3(512), 0, st, p);
+    hipLaunchKernelGGL((mfma_fp4_kernel<KA, KB, 2, 4, 1, 4, 2, 16, (CONV ? 2 : 4), CONV>), dim3(grid), dim3(512), 0, st, p);
 }
 
 bool launch_mfma256(const MfmaParams &p, int kindA, int kindB, bool conv, unsigned grid, hipStream_t st)

@@ -5,7 +5,8 @@
 //
 // CDNA4 has no 1-bit matrix instruction, but its FP4 (E2M1) matrix instruction
 // represents exactly what one or two bit planes of an operand can encode:
-// {0,1,2,3} and {-1,+1}.  The operands stay in the packed bit-plane layouts of
+// {0,1,2,3} (as the halves 0, 0.5, 1, 1.5, whose codes are the two plane bits
+// themselves) and {-1,+1}.  The operands stay in the packed bit-plane layouts of
 // the ABI in HBM and in LDS (Sec. 4.2 (a) data organisation, Sec. 4.1 (a)
 // shared-memory caching).  An operand of more than two bits is cut into base-4
 // digits of two adjacent planes (a last single plane counts as a digit with a
@@ -63,6 +64,7 @@ struct MfmaParams {
     int Kw;                  // words per plane along K
     int nk;                  // K chunks of KC words
     int c0;                  // additive correction (pad positions of a -1/+1 x -1/+1 product)
+    float out_scale;         // 2^(number of two-plane operands): those enter the matrix unit as value / 2
     // convolution geometry of the A operand (conv mode only)
     int H, W, Cw, R, S, stride, pad, Ho, Wo;
     float invCw;
@@ -103,14 +105,13 @@ template <int KIND> __device__ __forceinline__ void expand_fp4(uint32_t x0, uint
         out[1] = (~(x0 << 2) & k.m8) | k.m2;
         out[2] = (~(x0 << 1) & k.m8) | k.m2;
         out[3] = (~x0 & k.m8) | k.m2;
-    } else {                                    // 0,1,2,3 -> 0000, 0010, 0100, 0101
-        const uint32_t m0 = x0 & x1, m1 = x0 & ~x1;
-        // bit 2 <- x1, bit 1 <- x0 & ~x1, bit 0 <- x0 & x1; bit-field inserts keep bit 3 clear
-        uint32_t t;
-        t = (x1 << 2) & k.m4; t = (t & ~k.m2) | ((m1 << 1) & k.m2); out[0] = (t & ~k.m1) | (m0 & k.m1);
-        t = (x1 << 1) & k.m4; t = (t & ~k.m2) | (m1 & k.m2);        out[1] = (t & ~k.m1) | ((m0 >> 1) & k.m1);
-        t = x1 & k.m4;        t = (t & ~k.m2) | ((m1 >> 1) & k.m2); out[2] = (t & ~k.m1) | ((m0 >> 2) & k.m1);
-        t = (x1 >> 1) & k.m4; t = (t & ~k.m2) | ((m1 >> 2) & k.m2); out[3] = (t & ~k.m1) | ((m0 >> 3) & k.m1);
+    } else {                                    // v = 2 x1 + x0 -> code x1 x0 = v / 2 (0, 0.5, 1, 1.5):
+        // the two planes ARE the FP4 code of half the value, so no recoding is needed;
+        // the host-set out_scale (2 per two-plane operand) restores the factor exactly
+        out[0] = ((x1 << 1) & k.m2) | (x0 & k.m1);
+        out[1] = (x1 & k.m2) | ((x0 >> 1) & k.m1);
+        out[2] = ((x1 >> 1) & k.m2) | ((x0 >> 2) & k.m1);
+        out[3] = ((x1 >> 2) & k.m2) | ((x0 >> 3) & k.m1);
     }
     out[4] = out[5] = out[6] = out[7] = 0;
 }
@@ -132,7 +133,7 @@ __device__ __forceinline__ void finish_value(const MfmaParams &p, float v, int g
 {
     const bool rok = gm < p.M, cok = gn < p.N;
     const int wcol = gn >> 5;                   // word column of this lane's channel (the 32-wide tile shares it)
-    const int y = static_cast<int>(v) + p.c0;
+    const int y = static_cast<int>(v * p.out_scale) + p.c0;      // exact: v is a multiple of 1 / out_scale
     if (p.Y && rok && cok) p.Y[static_cast<int64_t>(gm) * p.N + gn] = y;
     if (p.scale) {
         float t = __fmaf_rn(sc, static_cast<float>(y), bi);
@@ -389,6 +390,34 @@ void mfma_fp4_kernel(const MfmaParams p)
     };
 
     if constexpr (NSPLIT == 1) {
+        constexpr int SLAB_STRIDE = BN + 4;                     // words; the pad keeps the two lane halves on different banks
+        constexpr bool SLAB_FITS = NWM * 32 * SLAB_STRIDE <= TILE_WORDS;
+        if (SLAB_FITS && p.Y && !p.scale && (p.N & 3) == 0) {
+            // Plain int32 output: a lane's accumulators are 128-byte row fragments
+            // scattered over 16 rows per tile.  They are transposed through LDS (one
+            // slab of 32 rows per wave row at a time; the operand tiles are dead) so
+            // that the stores leave as whole BN-column row segments, 16 bytes per lane.
+            int32_t *slab = reinterpret_cast<int32_t *>(smem);
+            static_for<FM>([&](auto ic) {
+                constexpr int i = decltype(ic)::value;
+                __syncthreads();                                // previous slab has been read
+                static_for<FN * 16>([&](auto jrc) {
+                    constexpr int j = decltype(jrc)::value / 16, r = decltype(jrc)::value % 16;
+                    const int srow = wm * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
+                    slab[srow * SLAB_STRIDE + wn * FN * 32 + j * 32 + lr] =
+                        static_cast<int>(acc[i][j][r] * p.out_scale) + p.c0;
+                });
+                __syncthreads();
+                for (int v = tid; v < NWM * 32 * (BN / 4); v += NT) {
+                    const int srow = v / (BN / 4), c4 = (v % (BN / 4)) * 4;
+                    const int gm = m0 + (srow >> 5) * FM * 32 + i * 32 + (srow & 31), gn = n0 + c4;
+                    if (gm < p.M && gn < p.N)
+                        *reinterpret_cast<int4 *>(p.Y + static_cast<int64_t>(gm) * p.N + gn) =
+                            *reinterpret_cast<const int4 *>(&slab[srow * SLAB_STRIDE + c4]);
+                }
+            });
+            return;
+        }
         // compile-time indices keep the accumulators in registers
         static_for<FN>([&](auto jc) {
             constexpr int j = decltype(jc)::value;

@@ -21,6 +21,6 @@ bool launch_mfma_small_conv(const MfmaParams &p, int kindA, int kindB, int vw, i
 bool launch_mfma_small_matrix(const MfmaParams &p, int kindA, int kindB, int nsplit, unsigned grid, hipStream_t st);
 
 // K words per chunk of each tile size (must match the instances).
-constexpr int mfma_chunk_words(int tile) { return tile == 256 ? 8 : tile == 128 ? 16 : 32; }
+constexpr int mfma_chunk_words(int tile) { return tile == 256 ? 16 : tile == 128 ? 16 : 32; }
 
 }  // namespace apnn
