@@ -66,6 +66,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-extra", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--network-only", type=int, default=0, metavar="N",
+                    help="run only N eager forward passes of the ResNet-18-shaped network (for rocprofv3 kernel traces)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch one 256 MiB apnn_probe_copy (reference for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -81,6 +83,16 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+    if args.network_only > 0:
+        from paper_2106_12169_amd.network import PackedNet
+        layers = wl.resnet18_layers()
+        net = PackedNet(layers, wl.network_params(layers), 8)
+        img = dev(wl.image_batch(2004, 8, 224))
+        for _ in range(args.network_only):
+            net.forward(img)
+        torch.cuda.synchronize()
+        return
 
     wk = wl.CONFIG1
     Wv, Xv = wk.weights(), wk.activations()
@@ -145,7 +157,10 @@ def main():
             "achieved": round(flops / gemm_s / 1e12, 1), "peak": MFMA_FP4_PEAK / 1e12, "unit": "TFLOP/s",
             "frac": round(flops / gemm_s / MFMA_FP4_PEAK, 4),
             "kernel_us": round(gemm_s * 1e6, 2),
-            "traffic": None,
+            # HBM bytes per launch from rocprofv3 FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 (KiB), see
+            # profiles/mfma_fp4_kernel_gemm_w1a2_4096_hbm_counters.txt; algorithmic: 6 MiB in + 64 MiB out
+            "traffic": 12399.5 * 2.0 * 1024 + 69632.0 * 1024,
+            "algorithmic_bytes": (wk.M * wk.p + wk.N * wk.q) * (wk.K // 8) + 4 * wk.M * wk.N,
         },
         "roofline_popcount_kernel": {
             "bound": "alu", "kernel": "tile_kernel<4,4,16,4,4,false,false> (64x64 tile, v_and + v_bcnt), APNN_MFMA=0",
@@ -153,6 +168,7 @@ def main():
             "unit": "T lane-op/s (32-bit VALU, 2 lane-ops per 32 bit-products per plane pair)",
             "frac": round(lane_ops / pop_s / VALU_PEAK_LANE_OPS, 4),
             "kernel_us": round(pop_s * 1e6, 2), "eff_tops": round(wk.effective_ops / pop_s / 1e12, 1),
+            "traffic": 8300.7 * 2.0 * 1024 + 65536.0 * 1024,
         },
     }
 
