@@ -7,6 +7,13 @@
  *   every plane pair is multiplied with AND (or XOR) + popcount (Sec. 3.2,
  *   Cases I-III) and the pq partial results are shift-added by 2^(s+t)
  *   (Sec. 3.1), which equals the plain integer product "Y = WX".
+ *   The library holds two implementations of that product over the same
+ *   packed planes, with identical (exact integer) results: the plane-pair
+ *   AND/XOR + popcount form above, and a form that feeds two adjacent planes
+ *   at a time, as 4-bit floating-point codes, to the matrix instruction and
+ *   shift-adds base-4 digit pairs instead of bit pairs.  The second is used
+ *   whenever every partial sum stays exactly representable in fp32; the
+ *   choice is invisible at this interface.
  *
  * Conventions shared by every entry point
  *   - Pointers named *_dev are CALLER-OWNED DEVICE memory (e.g. a PyTorch
