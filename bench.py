@@ -153,7 +153,7 @@ def main():
         "config": {"workload": "config1: w1a2 GEMM M=N=K=4096, +-1 weights x unsigned 2-bit activations, int32 out",
                    "step": "apnn_pack(activations) + apnn_gemm", "seeds": [wk.seedW, wk.seedX]},
         "roofline": {
-            "bound": "mfma", "kernel": "mfma_fp4_kernel<PM1,U2> (v_mfma_scale_f32_32x32x64_f8f6f4, FP4 E2M1)",
+            "bound": "mfma", "kernel": "mfma_big_kernel<PM1,U2> (v_mfma_scale_f32_32x32x64_f8f6f4, FP4 E2M1)",
             "achieved": round(flops / gemm_s / 1e12, 1), "peak": MFMA_FP4_PEAK / 1e12, "unit": "TFLOP/s",
             "frac": round(flops / gemm_s / MFMA_FP4_PEAK, 4),
             "kernel_us": round(gemm_s * 1e6, 2),

@@ -77,6 +77,10 @@ static bool try_mfma(const Problem &pr, MfmaParams &mp, void *stream, int &rc)
     mp.out_scale = (kA == OPK_U2 ? 2.0f : 1.0f) * (kB == OPK_U2 ? 2.0f : 1.0f);
     // 0 pad bits of two -1/+1 operands multiply to +1 at every padded K position
     int t = pick_mfma_tile(pr.M, pr.N, pr.conv);
+    if (t == 256) {                             // that kernel addresses operands and output with 31-bit byte offsets
+        const int64_t lim = int64_t(1) << 31;
+        if (4 * pr.M * pr.PA * mp.ldwA >= lim || 4 * pr.N * pr.PB * mp.ldwB >= lim || 4 * (pr.M + 256) * pr.N >= lim) t = 128;
+    }
     const bool short_k = !pr.conv && mp.Kw <= 8 && t <= 64;      // 8-word chunks: no step multiplies padding
     if (short_k) t = 64;
     const int kc = short_k ? 8 : mfma_chunk_words(t);

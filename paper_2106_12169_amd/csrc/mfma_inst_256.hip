@@ -1,11 +1,13 @@
-// Instances of the FP4 matrix-core kernel with a 256 x 256 block tile.
+// Instances of the large-product matrix-core kernel (256 x 256 block tile, 4 waves of 128 x 128).
+#include "mfma_big.h"
 #include "mfma_launch.h"
 
 namespace apnn {
 
 template <int KA, int KB, bool CONV> static void go(const MfmaParams &p, unsigned grid, hipStream_t st)
 {
-    hipLaunchKernelGGL((mfma_fp4_kernel<KA, KB, 2, 4, 1, 4, 2, 16, (CONV ? 2 : 4), CONV>), dim3(grid), dim3(512), 0, st, p);
+    static_assert(!CONV, "matrix operands only");
+    hipLaunchKernelGGL((mfma_big_kernel<KA, KB, 2, 2, 4, 4>), dim3(grid), dim3(256), 0, st, p);
 }
 
 bool launch_mfma256(const MfmaParams &p, int kindA, int kindB, bool conv, unsigned grid, hipStream_t st)

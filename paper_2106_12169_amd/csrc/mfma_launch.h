@@ -5,7 +5,7 @@
 
 namespace apnn {
 
-// tile: 256 (256 x 256 block, 8 waves), 128 (128 x 128, 4 waves), 64 (64 x 64, 4 waves),
+// tile: 256 (256 x 256 block, 4 waves, mfma_big_kernel), 128 (128 x 128, 4 waves), 64 (64 x 64, 4 waves),
 // 32 (32 x 32, 4 waves splitting K).
 // Returns false if the combination is not instantiated.
 bool launch_mfma256(const MfmaParams &p, int kindA, int kindB, bool conv, unsigned grid, hipStream_t st);
