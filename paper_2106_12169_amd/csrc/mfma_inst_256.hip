@@ -1,32 +1,23 @@
-// Instances of the large-product matrix-core kernel (256 x 256 block tile, 4 waves of 128 x 128).
-#include "mfma_big.h"
+// Dispatcher of the large-product matrix-core kernel (256 x 256 block tile, 4 waves
+// of 128 x 128); the instances live in one translation unit per A-operand kind so
+// that they compile in parallel.
 #include "mfma_launch.h"
 
 namespace apnn {
 
-template <int KA, int KB, bool CONV> static void go(const MfmaParams &p, unsigned grid, hipStream_t st)
-{
-    static_assert(!CONV, "matrix operands only");
-    hipLaunchKernelGGL((mfma_big_kernel<KA, KB, 2, 2, 4, 4>), dim3(grid), dim3(256), 0, st, p);
-}
+bool launch_mfma256_u1(const MfmaParams &p, int kindB, unsigned grid, hipStream_t st);
+bool launch_mfma256_u2(const MfmaParams &p, int kindB, unsigned grid, hipStream_t st);
+bool launch_mfma256_pm1(const MfmaParams &p, int kindB, unsigned grid, hipStream_t st);
 
 bool launch_mfma256(const MfmaParams &p, int kindA, int kindB, bool conv, unsigned grid, hipStream_t st)
 {
-    if (!conv) {
-        switch (kindA * 3 + kindB) {
-            case 0: go<0, 0, false>(p, grid, st); return true;
-            case 1: go<0, 1, false>(p, grid, st); return true;
-            case 2: go<0, 2, false>(p, grid, st); return true;
-            case 3: go<1, 0, false>(p, grid, st); return true;
-            case 4: go<1, 1, false>(p, grid, st); return true;
-            case 5: go<1, 2, false>(p, grid, st); return true;
-            case 6: go<2, 0, false>(p, grid, st); return true;
-            case 7: go<2, 1, false>(p, grid, st); return true;
-            case 8: go<2, 2, false>(p, grid, st); return true;
-            default: return false;
-        }
+    if (conv) return false;              // instantiated for matrix operands only
+    switch (kindA) {
+        case OPK_U1: return launch_mfma256_u1(p, kindB, grid, st);
+        case OPK_U2: return launch_mfma256_u2(p, kindB, grid, st);
+        case OPK_PM1: return launch_mfma256_pm1(p, kindB, grid, st);
+        default: return false;
     }
-    return false;                        // large tiles are instantiated for matrix operands only
 }
 
 }  // namespace apnn
