@@ -21,7 +21,8 @@
 //     after each matrix instruction of step s, each fenced against instruction
 //     scheduling; shifts work on the words of two consecutive steps at once
 //     (64-bit shifts: the bits that cross between the words fall outside the masks);
-//   - the int32 output leaves through wave-private LDS slabs as whole row segments.
+//   - the int32 output is stored straight from the accumulators with range-checked
+//     buffer stores (two 128-byte row segments per instruction, no branches, no waits).
 #pragma once
 #include "mfma_kernel.h"
 
@@ -148,11 +149,7 @@ __global__ __launch_bounds__(64 * NWM * NWN, 1) void mfma_big_kernel(const MfmaP
 
     constexpr int A_WORDS = BM * RSA, B_WORDS = BN * RSB;
     constexpr int TILE_WORDS = 2 * A_WORDS + 2 * B_WORDS;
-    constexpr int WN = FN * 32;                         // columns of a wave tile
-    constexpr int SLAB_STRIDE = WN + 4;                 // words per row of an output slab (epilogue)
-    constexpr int SLAB_WORDS = NW * 32 * SLAB_STRIDE;
-    // A buffer 0, A buffer 1, B buffer 0, B buffer 1; the epilogue's output slabs reuse the space
-    __shared__ __attribute__((aligned(1024))) uint32_t smem[TILE_WORDS > SLAB_WORDS ? TILE_WORDS : SLAB_WORDS];
+    __shared__ __attribute__((aligned(1024))) uint32_t smem[TILE_WORDS];   // A buffer 0, A buffer 1, B buffer 0, B buffer 1
     typedef __attribute__((address_space(3))) uint32_t *lds_ptr_t;
     const uint32_t smem_base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_ptr_t)smem));   // LDS byte address of the arena
 
@@ -397,43 +394,27 @@ __global__ __launch_bounds__(64 * NWM * NWN, 1) void mfma_big_kernel(const MfmaP
         step(I1{}, ea1, eb1, sa, sb, wa0, wb0, I0{}, ea0, eb0, wa0, wb0, I0{}, no_hook);
         advance(cda, cdb, ck);
     }
-    __builtin_amdgcn_s_waitcnt(VMCNT0);                 // no load may land in LDS once the epilogue reuses it
+    __builtin_amdgcn_s_waitcnt(VMCNT0);                 // the loads issued for chunks beyond the last one have landed
 
     // ---- epilogue
-    if (p.Y && !p.scale && (p.N & 3) == 0) {
-        // Plain int32 output.  A lane's accumulators are 128-byte row fragments
-        // scattered over 16 rows per tile; every wave transposes them through an LDS
-        // slab of its own (32 rows x WN columns at a time, rows padded by 4 words, which
-        // keeps the two lane halves on different banks; the operand tiles are dead),
-        // so that the stores leave as whole WN-column row segments, 16 bytes per lane.
-        // A wave's LDS accesses are served in order, so no barrier is needed between
-        // its writes and reads, and the waves of a block drain independently.
-        __syncthreads();                                // every wave is done with the operand tiles
-        int32_t *slab = reinterpret_cast<int32_t *>(smem) + wave * 32 * SLAB_STRIDE;
-        const int row_l = lane / (WN / 4), c4_l = (lane % (WN / 4)) * 4;       // this lane's (row, column) in a 64-vector sweep
-        constexpr int ROWS_PER_SWEEP = 64 / (WN / 4), SWEEPS = 32 / ROWS_PER_SWEEP;
-        // Buffer stores: rows beyond M fall outside the descriptor and are dropped by
-        // the hardware; columns beyond N are sent out of range explicitly.  The host
-        // guarantees (M + BM) N 4 < 2^31.
+    if (p.Y && !p.scale) {
+        // Plain int32 output, straight from the accumulators: register r of tile (i, j)
+        // is row 8 (r / 4) + 4 lh + r % 4, column lr, so one store instruction writes two
+        // whole 128-byte row segments.  Buffer stores: rows beyond M fall outside the
+        // descriptor and are dropped by the hardware, columns beyond N are sent out of
+        // range explicitly; no branches, no waits, the stores stream out behind the
+        // conversions.  The host guarantees (M + BM) N 4 < 2^31.
         const __amdgpu_buffer_rsrc_t rsrcY =
             __builtin_amdgcn_make_buffer_rsrc(p.Y, 0, 4u * static_cast<uint32_t>(p.M) * p.N, 0x00020000);
-        const int gn = n0 + wn * WN + c4_l;
-        const uint32_t voffY = (4u * (static_cast<uint32_t>(m0 + wm * FM * 32 + row_l) * p.N + gn)) | (gn < p.N ? 0u : OUT_OF_RANGE);
-        static_for<FM>([&](auto ic) {
-            constexpr int i = decltype(ic)::value;
-            static_for<FN * 16>([&](auto jrc) {
-                constexpr int j = decltype(jrc)::value / 16, r = decltype(jrc)::value % 16;
-                slab[(8 * (r >> 2) + 4 * lh + (r & 3)) * SLAB_STRIDE + j * 32 + lr] = static_cast<int>(acc[i][j][r]) + p.c0;
-            });
-            v4u_t rows[SWEEPS];
-            static_for<SWEEPS>([&](auto sc) {
-                constexpr int sw = decltype(sc)::value;
-                rows[sw] = *reinterpret_cast<const v4u_t *>(&slab[(sw * ROWS_PER_SWEEP + row_l) * SLAB_STRIDE + c4_l]);
-            });
-            static_for<SWEEPS>([&](auto sc) {
-                constexpr int sw = decltype(sc)::value;
-                __builtin_amdgcn_raw_buffer_store_b128(rows[sw], rsrcY, voffY, 4 * (i * 32 + sw * ROWS_PER_SWEEP) * p.N, 0);
-            });
+        const int gn0 = n0 + wn * FN * 32 + lr;
+        const uint32_t vbase = 4u * (static_cast<uint32_t>(m0 + wm * FM * 32 + 4 * lh) * p.N + gn0);
+        uint32_t voffY[FN];
+#pragma unroll
+        for (int j = 0; j < FN; ++j) voffY[j] = (vbase + 128u * j) | (gn0 + 32 * j < p.N ? 0u : OUT_OF_RANGE);
+        static_for<FM * FN * 16>([&](auto c) {
+            constexpr int i = decltype(c)::value / (FN * 16), j = decltype(c)::value / 16 % FN, r = decltype(c)::value % 16;
+            constexpr int row = i * 32 + 8 * (r >> 2) + (r & 3);
+            __builtin_amdgcn_raw_buffer_store_b32(static_cast<int>(acc[i][j][r]) + p.c0, rsrcY, voffY[j], 4 * row * p.N, 0);
         });
         return;
     }
