@@ -224,6 +224,25 @@ def extra_configs(B, wl, dev, graph_time):
                                 "fp4_mfma_frac": round(c.effective_ops / t / MFMA_FP4_PEAK, 4),
                                 "what": "fused conv + scale/bias + requantise + repack, packed in/out (latency bound)"}
 
+    # Layer shapes of the paper's own APMM / APConv evaluation (Sec. 6.1): device time per launch.
+    # Its raw-latency table (64 x 1024 x 1024, RTX 3090) reads 6.67 / 6.81 / 7.06 / 7.15 us for
+    # w1a2 / w1a3 / w1a4 / w2a2 -- another machine, quoted as context only.
+    fc = {}
+    for (w, a) in wl.PAPER_FC_BITS:
+        fc[f"w{w}a{a}"] = {str(dim): gemm_case(wl.paper_fc_workload(w, a, dim))["us"] for dim in wl.PAPER_FC_DIMS}
+    ex["paper_fc_batch64_us_by_dim"] = fc
+    cv = {}
+    for ch in wl.PAPER_CONV_CHANNELS:
+        c = wl.paper_conv_workload(ch)
+        d = B.Conv(c.BS, c.H, c.W, c.Cin, c.Cout, c.R, c.S, c.stride, c.pad, c.p, c.q, c.encW, c.encX)
+        Wp = B.apnn_pack_conv_weights(dev(c.weights_oihw()), c.p, c.encW)
+        Xp = B.apnn_pack_fmap(dev(c.features_nchw()), B.LAYOUT_NCHW, c.q, c.encX)
+        sc, bi = dev(c.scale()), dev(c.bias())
+        outp = torch.empty(B.apnn_fmap_words(d.N * d.Ho * d.Wo, c.Cout, c.q_out), dtype=torch.int32, device="cuda")
+        t = graph_time(lambda: B.apnn_layer(d, Wp, Xp, q_out=c.q_out, scale=sc, bias=bi, out=outp))
+        cv[str(ch)] = round(t * 1e6, 2)
+    ex["paper_conv_w1a2_16x16_batch1_us_by_channels"] = cv
+
     layers = wl.resnet18_layers()
     net = PackedNet(layers, wl.network_params(layers), 8)
     img = dev(wl.image_batch(2004, 8, 224))

@@ -120,6 +120,18 @@ def sweep_workload(w: int, a: int, n: int = 2048) -> GemmWorkload:
 
 CONFIG2 = tuple(sweep_workload(w, a) for (w, a) in SWEEP_BITS)
 
+# Fully-connected layer shapes of the APMM evaluation (Sec. 6.1.1): batch 64, input = output
+# dimension in {128, 256, ..., 1024}; the raw-latency table uses 64 x 1024 x 1024.  Weights are
+# the M rows (output neurons), the batch supplies the N rows.  Bit combinations: those named in
+# that section and its latency table (unsigned x unsigned, as in the precision sweep).
+PAPER_FC_DIMS: Tuple[int, ...] = tuple(range(128, 1025, 128))
+PAPER_FC_BITS: Tuple[Tuple[int, int], ...] = ((1, 2), (1, 3), (1, 4), (2, 2))
+
+
+def paper_fc_workload(w: int, a: int, dim: int, batch: int = 64) -> GemmWorkload:
+    return GemmWorkload(f"fc_w{w}a{a}_{batch}x{dim}x{dim}", dim, batch, dim, w, a, ENC_UNSIGNED, ENC_UNSIGNED,
+                        5000 + 16 * w + a + dim, 6000 + 16 * w + a + dim)
+
 
 # --------------------------------------------------------------------------
 # Convolution workload (benchmark configuration 3)
@@ -172,6 +184,15 @@ class ConvWorkload:
     def effective_ops(self) -> float:
         return 2.0 * self.BS * self.Ho * self.Wo * self.Cout * self.Cin * self.R * self.S
 
+
+def paper_conv_workload(channels: int, w: int = 1, a: int = 2) -> "ConvWorkload":
+    """Convolution shape of the APConv evaluation (Sec. 6.1.2): 16 x 16 feature map, 3 x 3 filter,
+    stride 1, batch 1, input = output channels in {128, ..., 1024}; fused 2-bit output."""
+    return ConvWorkload(f"conv_w{w}a{a}_1x{channels}x16x16", 1, channels, 16, 16, channels, 3, 3, 1, 1, w, a,
+                        ENC_UNSIGNED if w > 1 else ENC_PM1, ENC_UNSIGNED, 2, 7000 + channels + 16 * w + a)
+
+
+PAPER_CONV_CHANNELS: Tuple[int, ...] = (128, 256, 512, 1024)
 
 CONFIG3 = ConvWorkload("conv_w1a2_8x128x28x28", 8, 128, 28, 28, 128, 3, 3, 1, 1, 1, 2,
                        ENC_PM1, ENC_UNSIGNED, 2, 3)

@@ -130,3 +130,12 @@ def test_config2_full_size_sampled(w, a):
     assert np.array_equal(Y[rows], oracle.gemm(W[rows], U, w, X, U, a))
     colw = W.astype(np.int64).sum(0)
     assert np.array_equal(Y.astype(np.int64).sum(0), X.astype(np.int64) @ colw)
+
+
+@pytest.mark.parametrize("w,a", wl.PAPER_FC_BITS)
+@pytest.mark.parametrize("dim", [128, 640, 1024])
+def test_paper_fc_shapes(w, a, dim):
+    """Fully-connected shapes of the paper's APMM evaluation (batch 64, K = N = dim), default dispatch."""
+    wk = wl.paper_fc_workload(w, a, dim)
+    W, X = wk.weights(), wk.activations()
+    assert np.array_equal(gpu_gemm(W, U, w, X, U, a), oracle.gemm(W, U, w, X, U, a))

@@ -143,6 +143,26 @@ def test_config3_full_layer():
     assert len(np.unique(want_codes)) == 4
 
 
+@pytest.mark.parametrize("channels", wl.PAPER_CONV_CHANNELS)
+def test_paper_conv_shapes(channels):
+    """Convolution shapes of the paper's APConv evaluation (16 x 16 map, 3 x 3, stride 1, batch 1),
+    fused w1a2 layer, default dispatch; the scale is spread so that all four codes occur."""
+    c = wl.paper_conv_workload(channels)
+    Wv, Xv = c.weights_oihw(), c.features_nchw()
+    d = B.Conv(c.BS, c.H, c.W, c.Cin, c.Cout, c.R, c.S, c.stride, c.pad, c.p, c.q, c.encW, c.encX)
+    scale = (c.scale() / np.sqrt(9.0 * channels)).astype(np.float32)
+    bias = (c.bias() + 1.5).astype(np.float32)
+    acc = torch.empty((d.N, d.Ho, d.Wo, c.Cout), dtype=torch.int32, device="cuda")
+    out = B.apnn_layer(d, B.apnn_pack_conv_weights(dev(Wv), c.p, c.encW), B.apnn_pack_fmap(dev(Xv), B.LAYOUT_NCHW, c.q, c.encX),
+                       q_out=c.q_out, scale=dev(scale), bias=dev(bias), acc_out=acc)
+    torch.cuda.synchronize()
+    want_acc = oracle.conv2d(Wv, c.encW, c.p, Xv, c.encX, c.q, c.stride, c.pad)
+    assert np.array_equal(acc.cpu().numpy().transpose(0, 3, 1, 2), want_acc)
+    codes, _ = hp.unpack_fmap(hp.words_u32(out), d.N, d.Ho, d.Wo, c.Cout, c.q_out)
+    want_codes, _ = oracle.epilogue(want_acc, scale, bias, c.q_out)
+    assert np.array_equal(codes, want_codes) and len(np.unique(want_codes)) == 4
+
+
 def test_gemm_layer_fc_shape():
     """Fully connected layer: 8-bit activations x +-1 weights, int32 logits, ragged Cout."""
     BS, K, Cout = 8, 512, 1000
