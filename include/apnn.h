@@ -99,7 +99,7 @@ int apnn_pack_conv_weights(const void *src_dev, int64_t Cout, int64_t Cin, int R
 
 /* Input-layer packing for few input channels (S*C <= 32): every output
  * pixel gets the bits of its R x S x C receptive field, one 32-bit word per
- * kernel row r holding bit (s*C + c), frame overhang as 0 bits.  Source is an
+ * kernel row r holding bit (c*S + s), frame overhang as 0 bits.  Source is an
  * N x C x H x W image (one unsigned value per byte).  Result is a matrix
  * operand [N*Ho*Wo][bits][apnn_row_words(32*R)] that, multiplied with weights
  * packed by apnn_pack_patch_weights, equals the R x S convolution with

@@ -120,8 +120,81 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(const float *__restr
 }
 
 // Input-layer receptive-field packing: word r of an output pixel holds bit
-// (s*C + c) = bit t of image[n][c][ho*stride+r-pad][wo*stride+s-pad].  A block
-// handles 32 output pixels; thread (pixel, r) collects the S*C bytes of kernel row
+// (c*S + s) = bit t of image[n][c][ho*stride+r-pad][wo*stride+s-pad].
+//
+// Row kernel (the usual case).  With the taps of one channel adjacent in the word,
+// the S bits of (pixel, r, c, t) are S consecutive bits of the bit string "plane t of
+// image row h, channel c".  A block owns one output row (n, ho): it first splits the
+// R x C image rows it needs into plane bit strings in LDS (one thread per 32 pixels,
+// the same byte gather as the matrix packer; two zero words in front and behind take
+// the place of the frame overhang), then every thread assembles output words from
+// S-bit fields cut out of those strings with a funnel shift and writes them as
+// 16-byte vectors in destination order.  Per output word: C x (two LDS reads, one
+// funnel shift, one mask-and-insert) instead of S*C byte loads and gathers.
+__global__ __launch_bounds__(256) void pack_patches_rows_kernel(const uint8_t *__restrict__ img,
+                                                                uint32_t *__restrict__ dst, int C, int H, int W,
+                                                                int Ho, int Wo, int R, int S, int stride, int pad,
+                                                                int bits, int LDW, int RW)
+{
+    extern __shared__ uint32_t rows[];                  // [R][C][bits][RW]; the string starts at word 1
+    const int tid = threadIdx.x;
+    const int ho = blockIdx.x % Ho;
+    const int64_t n = blockIdx.x / Ho;
+    const int Ww = (W + 31) / 32;
+    for (int i = tid; i < R * C * bits * RW; i += 256) rows[i] = 0;
+    __syncthreads();
+    for (int item = tid; item < R * C * Ww; item += 256) {
+        const int j = item % Ww, rc = item / Ww, c = rc % C, r = rc / C;
+        const int h = ho * stride - pad + r;
+        if (h < 0 || h >= H) continue;
+        const uint8_t *src = img + ((n * C + c) * H + h) * static_cast<int64_t>(W) + 32 * j;
+        uint32_t d[8];
+        if (32 * j + 32 <= W && (reinterpret_cast<uintptr_t>(src) & 3u) == 0) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) d[i] = reinterpret_cast<const uint32_t *>(src)[i];
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                d[i] = 0;
+#pragma unroll
+                for (int b = 0; b < 4; ++b)
+                    if (32 * j + 4 * i + b < W) d[i] |= static_cast<uint32_t>(src[4 * i + b]) << (8 * b);
+            }
+        }
+        for (int t = 0; t < bits; ++t) {
+            uint32_t w = 0;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) w |= gather4((d[i] >> t) & 0x01010101u) << (4 * i);
+            rows[((r * C + c) * bits + t) * RW + 1 + j] = w;
+        }
+    }
+    __syncthreads();
+    const uint32_t field = (1u << S) - 1u;
+    const int Q = LDW / 4;                              // 16-byte vectors per (pixel, plane)
+    uint32_t *out = dst + (static_cast<int64_t>(blockIdx.x) * Wo) * bits * LDW;
+    for (int v = tid; v < Wo * bits * Q; v += 256) {
+        const int q = v % Q, t = (v / Q) % bits, wo = v / (Q * bits);
+        const int xb = wo * stride - pad + 32;          // bit position of tap s = 0 in the string (>= 0: pad <= 32)
+        const int wi = xb >> 5, sh = xb & 31;
+        uint32_t w4[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int r = 4 * q + k;
+            uint32_t w = 0;
+            if (r < R) {
+                for (int c = 0; c < C; ++c) {
+                    const uint32_t *str = &rows[((r * C + c) * bits + t) * RW + wi];
+                    w |= (__funnelshift_r(str[0], str[1], sh) & field) << (c * S);
+                }
+            }
+            w4[k] = w;
+        }
+        *reinterpret_cast<uint4 *>(out + static_cast<int64_t>(v) * 4) = make_uint4(w4[0], w4[1], w4[2], w4[3]);
+    }
+}
+
+// General kernel (any geometry that fits the word): a block handles 32 output
+// pixels; thread (pixel, r) collects the S*C bytes of kernel row
 // r four to a register, every plane takes one bit of each byte with the same
 // gather as the row packer, and the 32 x bits x ldw words of the block, which are
 // contiguous in the destination, leave through LDS as coalesced 16-byte stores.
@@ -135,7 +208,7 @@ __global__ __launch_bounds__(256) void pack_patches_kernel(const uint8_t *__rest
     const int tid = threadIdx.x;
     const int r = tid & 7, lp = tid >> 3;                // kernel row, pixel inside the block
     const int64_t pix = static_cast<int64_t>(blockIdx.x) * 32 + lp;
-    uint32_t d[8] = {0, 0, 0, 0, 0, 0, 0, 0};            // byte (s*C + c) of the kernel row, 4 per register
+    uint32_t d[8] = {0, 0, 0, 0, 0, 0, 0, 0};            // byte (c*S + s) of the kernel row, 4 per register
     if (pix < npix) {
         const int wo = static_cast<int>(pix % Wo);
         const int ho = static_cast<int>((pix / Wo) % Ho);
@@ -143,13 +216,13 @@ __global__ __launch_bounds__(256) void pack_patches_kernel(const uint8_t *__rest
         const int h = ho * stride + r - pad;
         if (r < R && h >= 0 && h < H) {
             const int x0 = wo * stride - pad;
-            int sc = 0, c = 0;                               // i = sc*C + c, stepped without dividing
+            int sc = 0, c = 0;                               // i = c*S + sc, stepped without dividing
 #pragma unroll
             for (int i = 0; i < 32; ++i) {
                 const int x = x0 + sc;
                 if (i < S * C && x >= 0 && x < W)
                     d[i >> 2] |= static_cast<uint32_t>(img[((n * C + c) * H + h) * W + x]) << (8 * (i & 3));
-                if (++c == C) { c = 0; ++sc; }
+                if (++sc == S) { sc = 0; ++c; }
             }
         }
     }
@@ -180,11 +253,11 @@ __global__ __launch_bounds__(256) void pack_patch_weights_kernel(const uint8_t *
             for (int c = 0; c < Cin; ++c) {
                 const uint8_t v = wsrc[((static_cast<size_t>(co) * Cin + c) * R + r) * S + s];
                 if (pm1) {
-                    w[0] |= static_cast<uint32_t>(static_cast<int8_t>(v) > 0) << (s * Cin + c);
+                    w[0] |= static_cast<uint32_t>(static_cast<int8_t>(v) > 0) << (c * S + s);
                 } else {
 #pragma unroll
                     for (int t = 0; t < 8; ++t)
-                        if (t < bits) w[t] |= ((static_cast<uint32_t>(v) >> t) & 1u) << (s * Cin + c);
+                        if (t < bits) w[t] |= ((static_cast<uint32_t>(v) >> t) & 1u) << (c * S + s);
                 }
             }
     }
@@ -281,6 +354,15 @@ extern "C" int apnn_pack_patches(const uint8_t *src_dev, int64_t N, int64_t C, i
     if (R > 8) return fail(APNN_ERR_UNSUPPORTED, "apnn_pack_patches: kernel height %d above 8", R);
     const int ldw = static_cast<int>(apnn_row_words(32 * static_cast<int64_t>(R)));
     const int64_t npix = N * Ho * Wo;
+    // row kernel: needs pad <= 32 (non-negative string positions) and the plane strings of R x C rows in LDS
+    const int rw = static_cast<int>((W + 31) / 32) + 4;
+    const size_t lds = static_cast<size_t>(R) * C * bits * rw * sizeof(uint32_t);
+    if (pad <= 32 && lds <= 48 * 1024 && N * Ho <= 0x7FFFFFFF && (N * C * H * W) < (int64_t(1) << 40)) {
+        hipLaunchKernelGGL(pack_patches_rows_kernel, dim3(static_cast<unsigned>(N * Ho)), dim3(256), lds, as_stream(stream),
+                           src_dev, dst_dev, static_cast<int>(C), static_cast<int>(H), static_cast<int>(W), Ho, Wo, R, S,
+                           stride, pad, bits, ldw, rw);
+        return check_launch("apnn_pack_patches");
+    }
     const unsigned grid = static_cast<unsigned>(ceil_div(npix, 32));
     hipLaunchKernelGGL(pack_patches_kernel, dim3(grid), dim3(256), 0, as_stream(stream), src_dev, dst_dev, npix,
                        static_cast<int>(C), static_cast<int>(H), static_cast<int>(W), Ho, Wo, R, S, stride, pad, bits, ldw);

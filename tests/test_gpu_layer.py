@@ -209,3 +209,31 @@ def test_first_layer_patches_equal_convolution():
     torch.cuda.synchronize()
     want = oracle.conv2d(Wv, P, 1, img, U, 8, 2, 3)
     assert np.array_equal(acc.cpu().numpy().reshape(BS, Ho, Ho, Cout).transpose(0, 3, 1, 2), want)
+
+
+@pytest.mark.parametrize("C,H,W,R,S,stride,pad,bits", [
+    (3, 38, 38, 7, 7, 2, 3, 8),        # the input layer's geometry
+    (1, 30, 41, 5, 5, 1, 2, 4),        # one channel, odd width (byte loads)
+    (3, 9, 33, 3, 3, 1, 1, 2),
+    (4, 19, 70, 3, 8, 3, 0, 8),        # S * C = 32 fills the word, stride 3, no padding
+    (2, 21, 64, 8, 8, 2, 3, 3),        # tallest kernel
+    (4, 9, 2100, 8, 8, 2, 3, 8),       # plane strings too large for LDS: general kernel
+])
+def test_patch_packer_geometries(C, H, W, R, S, stride, pad, bits):
+    """apnn_pack_patches x apnn_pack_patch_weights through the matrix kernel equals the convolution,
+    for both packer kernels and the edge geometries (overhang on every side, ragged widths)."""
+    BS, Cout = 2, 40
+    img = wl.uniform_codes(100 + C + W, (BS, C, H, W), bits)
+    Wv = wl.fair_signs(200 + R + S, (Cout, C, R, S))
+    Xp = B.apnn_pack_patches(dev(img), R, S, stride, pad, bits)
+    Wp = B.apnn_pack_patch_weights(dev(Wv), 1, P)
+    Ho, Wo = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+    d = B.Conv(BS * Ho * Wo, 1, 1, 32 * R, Cout, 1, 1, 1, 0, 1, bits, P, U)
+    acc = torch.empty((BS * Ho * Wo, Cout), dtype=torch.int32, device="cuda")
+    B.apnn_layer(d, Wp, Xp, is_gemm=True, acc_out=acc)
+    torch.cuda.synchronize()
+    want = oracle.conv2d(Wv, P, 1, img, U, bits, stride, pad)
+    assert np.array_equal(acc.cpu().numpy().reshape(BS, Ho, Wo, Cout).transpose(0, 3, 1, 2), want)
+    # pad words of the operand (kernel rows beyond R) are zero
+    words = hp.words_u32(Xp).reshape(BS * Ho * Wo, bits, -1)
+    assert (words[:, :, R:] == 0).all()
