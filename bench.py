@@ -6,15 +6,17 @@
 A step is one pass of the hot path on the headline workload (benchmark
 configuration 1: w1a2 GEMM, M = N = K = 4096, +-1 weights, unsigned 2-bit
 activations): bit-decompose and pack the activations, then the bit-plane GEMM
-(plane-pair AND + popcount, shift-add, Case III recovery) to int32.  Weights
-are packed once before timing (they are quantised at initialisation, Sec. 5.1).
-All inputs are resident in HBM when the timed region starts.
+to int32 (by default the FP4 matrix-core form of the plane-pair product; the
+literal AND + popcount form is timed as well).  Weights are packed once before
+timing (they are quantised at initialisation, Sec. 5.1).  All inputs are
+resident in HBM when the timed region starts.
 
 Prints ONE JSON line: effective TOPS (2 M N K / time), the roofline of the
-dominant kernel (VALU bitwise+popcount issue rate) measured with events around
-each of its launches inside the timed region, and the CPU oracle timed on a
-bounded row sample.  The other benchmark configurations are reported under
-"extra" (device time per launch via HIP-graph replay).
+dominant kernel (FP4 matrix peak) measured with events around each of its
+launches inside the timed region, the same for the AND + popcount kernel (VALU
+bitwise+popcount issue rate), and the CPU oracle timed on a bounded row sample.
+The other benchmark configurations and the paper's own layer shapes are
+reported under "extra" (device time per launch via HIP-graph replay).
 """
 import argparse
 import json
@@ -158,7 +160,7 @@ def main():
             "frac": round(flops / gemm_s / MFMA_FP4_PEAK, 4),
             "kernel_us": round(gemm_s * 1e6, 2),
             # HBM bytes per launch from rocprofv3 FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 (KiB), see
-            # profiles/mfma_fp4_kernel_gemm_w1a2_4096_hbm_counters.txt; algorithmic: 6 MiB in + 64 MiB out
+            # profiles/mfma_big_kernel_gemm_w1a2_4096_hbm_counters.txt; algorithmic: 6 MiB in + 64 MiB out
             "traffic": 11431.5 * 2.0 * 1024 + 67584.0 * 1024,
             "algorithmic_bytes": (wk.M * wk.p + wk.N * wk.q) * (wk.K // 8) + 4 * wk.M * wk.N,
         },
