@@ -133,12 +133,19 @@ typedef struct {
     int64_t N, H, W, Cin, Cout; /* batch, input frame, channels (Cin multiple of 32)    */
     int R, S, stride, pad;      /* kernel, stride, zero-contribution padding            */
     int p, q;                   /* weight bits, activation bits                         */
-    apnn_encoding encW, encX;   /* PM1 x PM1 is not implemented for conv (UNSUPPORTED)  */
+    apnn_encoding encW, encX;   /* -1/+1 features: see apnn_conv2d                      */
 } apnn_conv_desc;
 
 /* Y[n][ho][wo][co] = sum_{r,s,c} dec(W[co][c][r][s]) * dec(X[n][ho*stride+r-pad][wo*stride+s-pad][c]),
  * taps outside the frame contributing 0 (Sec. 4.2 (b)).  W_dev: conv-weight
- * layout; X_dev: fmap layout; Y_dev: int32 [N][Ho][Wo][Cout]. */
+ * layout; X_dev: fmap layout; Y_dev: int32 [N][Ho][Wo][Cout].
+ * -1/+1 features (Case II with -1/+1 weights, or the mirror of Case III with
+ * unsigned weights): a 0 bit means -1, so frame overhang cannot be left to the
+ * zero words of the loader; the matrix-instruction form gives every tap a
+ * validity word instead and is the only form that implements them.  It needs
+ * Cin to be a multiple of 64 and K max|w| < 2^24; otherwise, and whenever that
+ * form is switched off, such a call with pad > 0 (or with -1/+1 weights)
+ * returns APNN_ERR_UNSUPPORTED. */
 int apnn_conv2d(const apnn_conv_desc *desc, const uint32_t *W_dev, const uint32_t *X_dev,
                 int32_t *Y_dev, void *stream);
 

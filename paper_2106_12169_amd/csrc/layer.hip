@@ -72,11 +72,13 @@ static bool try_mfma(const Problem &pr, MfmaParams &mp, void *stream, int &rc)
     int64_t maxA, maxB;
     if (!mfma_kind(pr.PA, pr.encA, kA, mp.DA, maxA) || !mfma_kind(pr.PB, pr.encB, kB, mp.DB, maxB)) return false;
     if (pr.Ktotal <= 0 || round_up(pr.Ktotal, 1024) * maxA * maxB >= (int64_t(1) << 24)) return false;
-    if (pr.conv && (kA == OPK_PM1 || mp.Cw % 2 != 0)) return false;
+    if (pr.conv && mp.Cw % 2 != 0) return false;
+    if (pr.conv && kA == OPK_PM1) kA = OPK_PM1Z;         // -1/+1 features: taps outside the frame must contribute 0
     mp.PA = pr.PA; mp.PB = pr.PB;
     mp.out_scale = (kA == OPK_U2 ? 2.0f : 1.0f) * (kB == OPK_U2 ? 2.0f : 1.0f);
     // 0 pad bits of two -1/+1 operands multiply to +1 at every padded K position
     int t = pick_mfma_tile(pr.M, pr.N, pr.conv);
+    if (kA == OPK_PM1Z && t == 128) t = 64;              // instantiated for the 64-tile and the small-layer kernel
     if (t == 256) {                             // that kernel addresses operands and output with 31-bit byte offsets
         const int64_t lim = int64_t(1) << 31;
         if (4 * pr.M * pr.PA * mp.ldwA >= lim || 4 * pr.N * pr.PB * mp.ldwB >= lim || 4 * (pr.M + 256) * pr.N >= lim) t = 128;
@@ -122,8 +124,11 @@ static int run_tile(const Problem &pr, TileParams &p, int vw, void *stream)
     bool use_xor = false;
     p.alpha = 1; p.uA = 0; p.uB = 0; p.c0 = 0;
     const bool a_pm = pr.encA == APNN_ENC_PM1, b_pm = pr.encB == APNN_ENC_PM1;
+    if (pr.conv && a_pm && (b_pm || p.pad > 0))
+        return fail(APNN_ERR_UNSUPPORTED,
+                    "%s: -1/+1 features in a convolution need the matrix-core path (Cin a multiple of 64, K below 2^24 / max|w|)",
+                    pr.who);
     if (a_pm && b_pm) {                 // Case II:  K - 2 popc(XOR)
-        if (pr.conv) return fail(APNN_ERR_UNSUPPORTED, "%s: -1/+1 weights with -1/+1 features is not implemented for convolution", pr.who);
         use_xor = true; p.alpha = -2; p.c0 = static_cast<int>(pr.Ktotal);
     } else if (a_pm) {                  // Case III: 2 What X - J X, J X = row sum of the 0/1 operand
         p.alpha = 2; p.uB = -1;

@@ -47,7 +47,10 @@ bool launch_mfma64(const MfmaParams &p, int kindA, int kindB, bool conv, unsigne
             default: return false;
         }
     }
-    switch (kindA * 3 + kindB) {          // features are 0/1-encoded in convolution mode
+    switch (kindA * 3 + kindB) {          // features: 0/1 planes, or -1/+1 with the loader's validity word
+        case 9: go<3, 0, true>(p, grid, st); return true;
+        case 10: go<3, 1, true>(p, grid, st); return true;
+        case 11: go<3, 2, true>(p, grid, st); return true;
         case 0: go<0, 0, true>(p, grid, st); return true;
         case 1: go<0, 1, true>(p, grid, st); return true;
         case 2: go<0, 2, true>(p, grid, st); return true;

@@ -16,7 +16,10 @@ template <int KA, int KB> static void go(const MfmaParams &p, int vw, int nsplit
 
 bool launch_mfma_small_conv(const MfmaParams &p, int kindA, int kindB, int vw, int nsplit, unsigned grid, hipStream_t st)
 {
-    switch (kindA * 3 + kindB) {          // features are 0/1-encoded in convolution mode
+    switch (kindA * 3 + kindB) {          // features: 0/1 planes, or -1/+1 with the loader's validity word
+        case 9: go<3, 0>(p, vw, nsplit, grid, st); return true;
+        case 10: go<3, 1>(p, vw, nsplit, grid, st); return true;
+        case 11: go<3, 2>(p, vw, nsplit, grid, st); return true;
         case 0: go<0, 0>(p, vw, nsplit, grid, st); return true;
         case 1: go<0, 1>(p, vw, nsplit, grid, st); return true;
         case 2: go<0, 2>(p, vw, nsplit, grid, st); return true;

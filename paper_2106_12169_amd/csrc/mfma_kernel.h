@@ -53,7 +53,11 @@ namespace apnn {
 typedef int v8i_t __attribute__((ext_vector_type(8)));
 typedef float v16f_t __attribute__((ext_vector_type(16)));
 
-enum { OPK_U1 = 0, OPK_U2 = 1, OPK_PM1 = 2 };   // digit kinds: one 0/1 plane, two 0/1 planes, one -1/+1 plane
+// digit kinds: one 0/1 plane, two 0/1 planes, one -1/+1 plane, and (convolution features only) one -1/+1
+// plane accompanied by a validity word that the loader makes up: all ones for a tap inside the frame, zero
+// outside, so that taps outside the frame contribute 0 instead of -1 (zero-contribution padding of Sec. 4.2 (b)
+// for Case II and the mirrored Case III)
+enum { OPK_U1 = 0, OPK_U2 = 1, OPK_PM1 = 2, OPK_PM1Z = 3 };
 
 struct MfmaParams {
     const uint32_t *A, *B;   // row / column operand planes
@@ -105,6 +109,11 @@ template <int KIND> __device__ __forceinline__ void expand_fp4(uint32_t x0, uint
         out[1] = (~(x0 << 2) & k.m8) | k.m2;
         out[2] = (~(x0 << 1) & k.m8) | k.m2;
         out[3] = (~x0 & k.m8) | k.m2;
+    } else if (KIND == OPK_PM1Z) {              // as PM1 where x1 (all ones or zero) says the tap exists, else 0000 (0.0)
+        out[0] = ((~(x0 << 3) & k.m8) | k.m2) & x1;
+        out[1] = ((~(x0 << 2) & k.m8) | k.m2) & x1;
+        out[2] = ((~(x0 << 1) & k.m8) | k.m2) & x1;
+        out[3] = ((~x0 & k.m8) | k.m2) & x1;
     } else {                                    // v = 2 x1 + x0 -> code x1 x0 = v / 2 (0, 0.5, 1, 1.5):
         // the two planes ARE the FP4 code of half the value, so no recoding is needed;
         // the host-set out_scale (2 per two-plane operand) restores the factor exactly
@@ -162,7 +171,7 @@ __device__ __forceinline__ void finish_value(const MfmaParams &p, float v, int g
     }
 }
 
-template <int KIND> struct DigitPlanes { static constexpr int value = (KIND == OPK_U2) ? 2 : 1; };
+template <int KIND> struct DigitPlanes { static constexpr int value = (KIND == OPK_U2 || KIND == OPK_PM1Z) ? 2 : 1; };
 
 template <int KA, int KB, int NWM, int NWN, int NSPLIT, int FM, int FN, int KC, int VW, bool CONV>
 __global__ __launch_bounds__(64 * NWM * NWN * NSPLIT, (NWM * NWN * FM * FN >= 64 && FM * FN >= 16) ? 1 : 2)
@@ -221,7 +230,8 @@ void mfma_fp4_kernel(const MfmaParams p)
 #pragma unroll
         for (int u = 0; u < A_SLOTS; ++u) {
             const int v = tid + NT * u, c = v % CH, rp = v / CH;
-            const int row = rp / LA, plane = 2 * da * (LA - 1) + da * (2 - LA) + rp % LA;   // LA = 2: 2 da + pl; LA = 1: da
+            const bool validity = KA == OPK_PM1Z && rp % LA == 1;                  // made up, not loaded
+            const int row = rp / LA, plane = validity ? 0 : 2 * da * (LA - 1) + da * (2 - LA) + rp % LA;   // LA = 2: 2 da + pl; LA = 1: da
             const int gm = m0 + row, kk = kc * KC + c * VW;
             ra[u] = vec_zero<VW>();
             if (v < A_VECS && gm < p.M && kk < p.Kw && plane < p.PA) {
@@ -232,7 +242,8 @@ void mfma_fp4_kernel(const MfmaParams p)
                     const int h = a_h0[u] + r, w = a_w0[u] + sc;
                     if (h >= 0 && h < p.H && w >= 0 && w < p.W) {
                         const int64_t pix = a_pix[u] + h * p.W + w;
-                        ra[u] = *reinterpret_cast<const VecA *>(p.A + (pix * p.PA + plane) * p.Cw + cw);
+                        if (validity) ra[u] = vec_ones<VW>();
+                        else ra[u] = *reinterpret_cast<const VecA *>(p.A + (pix * p.PA + plane) * p.Cw + cw);
                     }
                 } else {
                     ra[u] = *reinterpret_cast<const VecA *>(p.A + (static_cast<int64_t>(gm) * p.PA + plane) * p.ldwA + kk);

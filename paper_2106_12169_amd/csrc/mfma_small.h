@@ -69,6 +69,8 @@ __global__ __launch_bounds__(256) void mfma_small_kernel(const MfmaParams p)
     // Words kk .. kk+3 of plane `plane` of this lane's A row (zero beyond Kw / outside the frame).
     auto load_a = [&](int plane, int kk) -> uint4 {
         uint4 v = make_uint4(0, 0, 0, 0);
+        const bool validity = KA == OPK_PM1Z && plane == 1;     // all ones for taps inside the frame, made up here
+        if (validity) plane = 0;
         if (!a_ok || kk >= p.Kw || plane >= p.PA) return v;
         if (CONV) {
             // VW = 4: the four words lie in one tap; VW = 2: two taps of two words each
@@ -82,7 +84,10 @@ __global__ __launch_bounds__(256) void mfma_small_kernel(const MfmaParams p)
                     const int h = a_h0 + r, w = a_w0 + sc;
                     if (h >= 0 && h < p.H && w >= 0 && w < p.W) {
                         const uint32_t *src = p.A + ((a_pix + h * p.W + w) * p.PA + plane) * p.Cw + cw;
-                        if (VW == 4) {
+                        if (validity) {
+                            if (VW == 4) v = make_uint4(~0u, ~0u, ~0u, ~0u);
+                            else if (part == 0) { v.x = ~0u; v.y = ~0u; } else { v.z = ~0u; v.w = ~0u; }
+                        } else if (VW == 4) {
                             v = *reinterpret_cast<const uint4 *>(src);
                         } else {
                             const uint2 t = *reinterpret_cast<const uint2 *>(src);

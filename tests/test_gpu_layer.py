@@ -72,11 +72,64 @@ def test_conv2d_matches_oracle(tile, Cin, Cout, H, Wd, R, stride, pad, encW, p, 
     assert np.array_equal(got, oracle.conv2d(Wv, encW, p, Xv, U, q, stride, pad))
 
 
-def test_conv_pm1_pm1_is_refused():
-    d = B.Conv(1, 8, 8, 32, 32, 3, 3, 1, 1, 1, 1, P, P)
-    e = torch.zeros(4096, dtype=torch.int32, device="cuda")
-    with pytest.raises(B.ApnnError) as ei:
-        B.apnn_conv2d(d, e, e)
+PM1_FEATURE_CONVS = [
+    # Cin, Cout, H, W, R, stride, pad, encW, p, BS
+    (64, 64, 14, 14, 3, 1, 1, P, 1, 2),          # Case II with padding: overhang taps must contribute 0, not -1
+    (128, 96, 9, 11, 3, 2, 1, P, 1, 1),          # stride 2, odd frame, Cout not a multiple of the tile
+    (64, 32, 8, 8, 1, 1, 0, P, 1, 2),            # 1x1, no padding
+    (64, 64, 7, 7, 5, 1, 2, U, 2, 1),            # mirrored Case III: unsigned 2-bit weights, two rings of overhang
+    (256, 64, 6, 6, 3, 1, 1, U, 1, 1),
+    (64, 64, 56, 56, 3, 1, 1, P, 1, 1),          # enough output pixels for the 64 x 64 block tile
+]
+
+
+@pytest.mark.parametrize("force", ["auto", "64", "32split1", "32split4"])
+@pytest.mark.parametrize("Cin,Cout,H,Wd,R,stride,pad,encW,p,BS", PM1_FEATURE_CONVS)
+def test_conv_with_pm1_features_matches_oracle(monkeypatch, force, Cin, Cout, H, Wd, R, stride, pad, encW, p, BS):
+    """-1/+1 features (Case II and the mirrored Case III) with zero-contribution padding."""
+    for v in ("APNN_TILE", "APNN_MFMA", "APNN_MFMA_TILE", "APNN_MFMA_SMALL", "APNN_MFMA_NSPLIT"):
+        monkeypatch.delenv(v, raising=False)
+    if force != "auto":
+        monkeypatch.setenv("APNN_MFMA_TILE", force[:2])
+        if force.startswith("32split"):
+            monkeypatch.setenv("APNN_MFMA_NSPLIT", force[-1])
+    Wv = wl.operand(41 + Cin + Cout, Cout, Cin * R * R, p, encW).reshape(Cout, Cin, R, R)
+    Xv = wl.fair_signs(42 + H, (BS, Cin, H, Wd))
+    d = B.Conv(BS, H, Wd, Cin, Cout, R, R, stride, pad, p, 1, encW, P)
+    Y = B.apnn_conv2d(d, B.apnn_pack_conv_weights(dev(Wv), p, encW), B.apnn_pack_fmap(dev(Xv), B.LAYOUT_NCHW, 1, P))
+    torch.cuda.synchronize()
+    assert np.array_equal(Y.cpu().numpy().transpose(0, 3, 1, 2), oracle.conv2d(Wv, encW, p, Xv, P, 1, stride, pad))
+
+
+def test_binary_network_chain():
+    """Two chained w1a1 layers: the first requantises to 1-bit codes, which the second reads as -1/+1."""
+    BS, C, H = 2, 64, 12
+    W1, W2 = wl.fair_signs(61, (C, C, 3, 3)), wl.fair_signs(62, (C, C, 3, 3))
+    Xv = wl.fair_signs(63, (BS, C, H, H))
+    scale = (wl.normals(64, (C,), 1.0, 0.2) / np.sqrt(9.0 * C)).astype(np.float32)
+    bias = wl.normals(65, (C,), 1.0, 0.3)
+    d = B.Conv(BS, H, H, C, C, 3, 3, 1, 1, 1, 1, P, P)
+    mid = B.apnn_layer(d, B.apnn_pack_conv_weights(dev(W1), 1, P), B.apnn_pack_fmap(dev(Xv), B.LAYOUT_NCHW, 1, P),
+                       q_out=1, scale=dev(scale), bias=dev(bias))
+    Y = B.apnn_conv2d(d, B.apnn_pack_conv_weights(dev(W2), 1, P), mid)
+    torch.cuda.synchronize()
+    codes, _ = oracle.epilogue(oracle.conv2d(W1, P, 1, Xv, P, 1, 1, 1), scale, bias, 1)
+    assert 0.2 < codes.mean() < 0.8
+    want = oracle.conv2d(W2, P, 1, (2 * codes.astype(np.int8) - 1), P, 1, 1, 1)
+    assert np.array_equal(Y.cpu().numpy().transpose(0, 3, 1, 2), want)
+
+
+def test_conv_with_pm1_features_refused_without_matrix_path(monkeypatch):
+    """The AND+popcount kernel has no zero-contribution padding for -1/+1 features: the call must fail, not be wrong."""
+    e = torch.zeros(1 << 16, dtype=torch.int32, device="cuda")
+    monkeypatch.setenv("APNN_MFMA", "0")
+    for d in (B.Conv(1, 8, 8, 64, 32, 3, 3, 1, 1, 1, 1, P, P), B.Conv(1, 8, 8, 64, 32, 3, 3, 1, 1, 2, 1, U, P)):
+        with pytest.raises(B.ApnnError) as ei:
+            B.apnn_conv2d(d, e, e)
+        assert ei.value.status == 2
+    monkeypatch.delenv("APNN_MFMA")
+    with pytest.raises(B.ApnnError) as ei:                      # one channel word: not a matrix-core shape
+        B.apnn_conv2d(B.Conv(1, 8, 8, 32, 32, 3, 3, 1, 1, 1, 1, P, P), e, e)
     assert ei.value.status == 2
 
 
