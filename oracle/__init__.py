@@ -33,6 +33,7 @@ def lib():
         _lib.orc_epilogue.argtypes = [vp, i64, i64, i64, vp, vp, vp, C.c_float, i32, vp, vp]
         _lib.orc_maxpool.argtypes = [vp, i64, i64, i64, i64, i32, i32, i32, vp]
         _lib.orc_sumpool.argtypes = [vp, i64, i64, i64, vp]
+        _lib.orc_gridpool.argtypes = [vp, i64, i64, i64, i64, i32, i32, vp]
     return _lib
 
 
@@ -156,4 +157,16 @@ def sumpool(codes):
     BS, Cc = c.shape[:2]
     out = np.empty((BS, Cc), np.uint8)
     _chk(lib().orc_sumpool(_p(c), BS, Cc, c.size // max(BS * Cc, 1), _p(out)))
+    return out
+
+
+POOL_MAX, POOL_SUM = 1, 2
+
+
+def gridpool(Y, k, mode):
+    """k x k grid pooling of int32 results BS x C x H x W (maximum or sum per grid; Sec. 5.2)."""
+    Y = np.ascontiguousarray(Y, np.int32)
+    BS, Cc, H, Wd = Y.shape
+    out = np.empty((BS, Cc, H // k, Wd // k), np.int32)
+    _chk(lib().orc_gridpool(_p(Y), BS, Cc, H, Wd, k, mode, _p(out)))
     return out

@@ -268,3 +268,28 @@ int orc_sumpool(const uint8_t *codes, int64_t BS, int64_t C, int64_t HW, uint8_t
     }
     return ORC_OK;
 }
+
+/* k x k grid pooling of int32 convolution results (Sec. 5.2: the feature map is
+ * split into k x k grids, one value per grid): mode 1 = maximum, mode 2 = sum
+ * (the average times k*k; the caller folds 1/(k*k) into the scale that
+ * follows).  Rows / columns that do not fill a grid are dropped. */
+int orc_gridpool(const int32_t *Y, int64_t BS, int64_t C, int64_t H, int64_t Wd, int k, int mode, int32_t *out)
+{
+    if (!Y || !out || k < 1 || (mode != 1 && mode != 2)) return ORC_ERR_ARG;
+    const int64_t Hp = H / k, Wp = Wd / k;
+    for (int64_t bc = 0; bc < BS * C; ++bc)
+        for (int64_t hp = 0; hp < Hp; ++hp)
+            for (int64_t wp = 0; wp < Wp; ++wp) {
+                int64_t acc = 0;
+                for (int dy = 0; dy < k; ++dy)
+                    for (int dx = 0; dx < k; ++dx) {
+                        const int64_t v = Y[(bc * H + hp * k + dy) * Wd + wp * k + dx];
+                        if (dy == 0 && dx == 0) acc = v;
+                        else if (mode == 1) acc = v > acc ? v : acc;
+                        else acc += v;
+                    }
+                if (acc > INT32_MAX || acc < INT32_MIN) return ORC_ERR_OVERFLOW;
+                out[(bc * Hp + hp) * Wp + wp] = (int32_t)acc;
+            }
+    return ORC_OK;
+}

@@ -18,7 +18,7 @@
  * Every function returns 0 on success, ORC_ERR_* otherwise.
  *
  * Pin status: orc_gemm, orc_conv2d, orc_apbit_gemm, orc_quantize,
- * orc_epilogue, orc_fold_bn, orc_maxpool, orc_sumpool are pinned by the
+ * orc_epilogue, orc_fold_bn, orc_maxpool, orc_sumpool, orc_gridpool are pinned by the
  * non-GPU tests (printed examples of Sec. 3.2, closed forms, brute force,
  * float64 library cross-checks).  The residual-network wiring built from
  * them in the tests is "parity unpinned": the paper gives no layer list for
@@ -86,6 +86,10 @@ int orc_maxpool(const uint8_t *codes, int64_t BS, int64_t C, int64_t H, int64_t 
 
 /* Global sum pooling of codes over H x W -> BS x C (must fit 8 bits). */
 int orc_sumpool(const uint8_t *codes, int64_t BS, int64_t C, int64_t HW, uint8_t *out);
+
+/* k x k grid pooling of int32 results BS x C x H x W -> BS x C x H/k x W/k
+ * (Sec. 5.2); mode 1 maximum, mode 2 sum; incomplete grids are dropped. */
+int orc_gridpool(const int32_t *Y, int64_t BS, int64_t C, int64_t H, int64_t Wd, int k, int mode, int32_t *out);
 
 #ifdef __cplusplus
 }

@@ -209,3 +209,25 @@ def test_small_residual_network_runs_and_uses_all_levels():
     with_res, _ = oracle.epilogue(acc, sc, bi, 2, res=out[L.res], res_scale=L.res_scale)
     without, _ = oracle.epilogue(acc, sc, bi, 2)
     assert np.array_equal(with_res, out[L.name]) and not np.array_equal(without, out[L.name])
+
+
+def test_gridpool_vs_library_and_by_hand():
+    """Grid pooling of int32 results: hand example, library max / average pooling, dropped ragged edges."""
+    Y = np.array([[[[1, -5, 7, 2, 9],
+                    [3, 4, -8, 0, 9],
+                    [-1, -2, 6, 6, 9],
+                    [-3, -4, 5, 7, 9],
+                    [100, 100, 100, 100, 100]]]], np.int32)             # 5 x 5: last row and column are dropped
+    assert oracle.gridpool(Y, 2, oracle.POOL_MAX).tolist() == [[[[4, 7], [-1, 7]]]]
+    assert oracle.gridpool(Y, 2, oracle.POOL_SUM).tolist() == [[[[3, 1], [-10, 24]]]]
+    rng = np.random.default_rng(5)
+    Z = rng.integers(-3000, 3000, (2, 3, 12, 10)).astype(np.int32)
+    zt = torch.from_numpy(Z.astype(np.float64))
+    for k in (2, 3):
+        want_max = torch.nn.functional.max_pool2d(zt, k, k).numpy()
+        want_sum = torch.nn.functional.avg_pool2d(zt, k, k).numpy() * (k * k)
+        assert np.array_equal(oracle.gridpool(Z, k, oracle.POOL_MAX), want_max.astype(np.int32))
+        assert np.array_equal(oracle.gridpool(Z, k, oracle.POOL_SUM), np.rint(want_sum).astype(np.int32))
+    assert np.array_equal(oracle.gridpool(Z, 1, oracle.POOL_MAX), Z) and np.array_equal(oracle.gridpool(Z, 1, oracle.POOL_SUM), Z)
+    with pytest.raises(oracle.OracleError):                               # sums must fit int32
+        oracle.gridpool(np.full((1, 1, 2, 2), 2**30, np.int32), 2, oracle.POOL_SUM)
