@@ -226,6 +226,18 @@ def extra_configs(B, wl, dev, graph_time):
                                 "fp4_mfma_frac": round(c.effective_ops / t / MFMA_FP4_PEAK, 4),
                                 "what": "fused conv + scale/bias + requantise + repack, packed in/out (latency bound)"}
 
+    # Fusion of pooling (Sec. 5.2; the paper's fusion experiment uses APConv-w1a2 + 2 x 2 pooling + 2-bit
+    # quantisation): one kernel against conv+requantise followed by the pooling kernel on packed codes.
+    pooled = torch.empty(B.apnn_fmap_words(d.N * (d.Ho // 2) * (d.Wo // 2), c.Cout, c.q_out), dtype=torch.int32, device="cuda")
+    t_f = graph_time(lambda: B.apnn_layer(d, Wp, Xp, q_out=c.q_out, scale=sc, bias=bi, out=pooled, pool=B.POOL_MAX2))
+
+    def two_kernels():
+        B.apnn_layer(d, Wp, Xp, q_out=c.q_out, scale=sc, bias=bi, out=outp)
+        B.apnn_maxpool(outp, d.N, d.Ho, d.Wo, c.Cout, c.q_out, 2, 2, 0, out=pooled)
+    t_u = graph_time(two_kernels)
+    ex["config3_conv_maxpool2_requant"] = {"fused_us": round(t_f * 1e6, 2), "two_kernels_us": round(t_u * 1e6, 2),
+                                           "what": "conv + 2x2 max pooling + 2-bit requantise: one kernel vs conv+requantise then pooling on codes"}
+
     # Layer shapes of the paper's own APMM / APConv evaluation (Sec. 6.1): device time per launch.
     # Its raw-latency table (64 x 1024 x 1024, RTX 3090) reads 6.67 / 6.81 / 7.06 / 7.15 us for
     # w1a2 / w1a3 / w1a4 / w2a2 -- another machine, quoted as context only.

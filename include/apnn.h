@@ -66,6 +66,8 @@ typedef enum {
 
 typedef enum { APNN_LAYOUT_NHWC = 0, APNN_LAYOUT_NCHW = 1 } apnn_layout;
 
+typedef enum { APNN_POOL_NONE = 0, APNN_POOL_MAX2 = 1, APNN_POOL_SUM2 = 2 } apnn_pool;
+
 /* Text of the last failure on this thread ("" if none).  Never NULL. */
 const char *apnn_last_error(void);
 
@@ -165,9 +167,18 @@ typedef struct {
     float res_scale;
     int32_t *acc_out_dev;  /* optional int32 [pixel][Cout] (raw accumulators)        */
     float *float_out_dev;  /* optional fp32  [pixel][Cout] (pre-floor values)        */
+    int pool;              /* APNN_POOL_NONE, or 2 x 2 grid pooling of the int32
+                              convolution results before scale/bias (Sec. 5.2):
+                              APNN_POOL_MAX2 maximum, APNN_POOL_SUM2 sum (= 4 x the
+                              average; fold 1/4 into scale).  "pixel" below then
+                              runs over [N][Ho/2][Wo/2]; incomplete grids of an
+                              odd Ho or Wo are dropped.  Convolutions only, and
+                              only in the matrix-instruction form of the product
+                              (APNN_ERR_UNSUPPORTED otherwise).                       */
 } apnn_layer_desc;
 
-/* For every output (pixel, co):
+/* For every output (pixel, co), Y being the convolution / GEMM result or, with
+ * pooling, the maximum / sum of the four results of the pixel's 2 x 2 grid:
  *   t    = fmaf(scale[co], (float)Y, bias[co]);
  *   t    = fmaf(res_scale, (float)res_code, t)            if residual_dev
  *   code = clamp(floor(t), 0, 2^q_out - 1)                (lower clamp = ReLU)

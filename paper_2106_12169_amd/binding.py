@@ -18,6 +18,7 @@ import torch
 
 ENC_UNSIGNED, ENC_PM1 = 0, 1
 LAYOUT_NHWC, LAYOUT_NCHW = 0, 1
+POOL_NONE, POOL_MAX2, POOL_SUM2 = 0, 1, 2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libapnn.so")
@@ -46,7 +47,7 @@ class LayerDesc(C.Structure):
     _fields_ = [("conv", ConvDesc), ("is_gemm", C.c_int), ("q_out", C.c_int),
                 ("scale_dev", C.c_void_p), ("bias_dev", C.c_void_p),
                 ("residual_dev", C.c_void_p), ("q_res", C.c_int), ("res_scale", C.c_float),
-                ("acc_out_dev", C.c_void_p), ("float_out_dev", C.c_void_p)]
+                ("acc_out_dev", C.c_void_p), ("float_out_dev", C.c_void_p), ("pool", C.c_int)]
 
 
 _lib = None
@@ -225,13 +226,13 @@ def apnn_layer(d: Conv, W: torch.Tensor, X: torch.Tensor, *, is_gemm: bool = Fal
                scale: Optional[torch.Tensor] = None, bias: Optional[torch.Tensor] = None,
                residual: Optional[torch.Tensor] = None, q_res: int = 0, res_scale: float = 0.0,
                acc_out: Optional[torch.Tensor] = None, float_out: Optional[torch.Tensor] = None,
-               out: Optional[torch.Tensor] = None) -> Optional[torch.Tensor]:
-    """Returns the packed output codes (or None when q_out == 0)."""
-    pixels = d.N * (1 if is_gemm else d.Ho * d.Wo)
+               out: Optional[torch.Tensor] = None, pool: int = 0) -> Optional[torch.Tensor]:
+    """Returns the packed output codes (or None when q_out == 0).  pool: POOL_NONE / POOL_MAX2 / POOL_SUM2."""
+    pixels = d.N * (1 if is_gemm else ((d.Ho // 2) * (d.Wo // 2) if pool else d.Ho * d.Wo))
     if q_out > 0 and out is None:
         out = _words(apnn_fmap_words(pixels, d.Cout, q_out), X.device)
     L = LayerDesc(d.c(), int(is_gemm), q_out, _ptr(scale), _ptr(bias), _ptr(residual), q_res, res_scale,
-                  _ptr(acc_out), _ptr(float_out))
+                  _ptr(acc_out), _ptr(float_out), pool)
     _check(lib().apnn_layer(C.byref(L), _ptr(W), _ptr(X), _ptr(out) if q_out > 0 else None, _stream()))
     return out if q_out > 0 else None
 

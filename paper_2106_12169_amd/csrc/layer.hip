@@ -71,7 +71,8 @@ static bool try_mfma(const Problem &pr, MfmaParams &mp, void *stream, int &rc)
     int kA, kB;
     int64_t maxA, maxB;
     if (!mfma_kind(pr.PA, pr.encA, kA, mp.DA, maxA) || !mfma_kind(pr.PB, pr.encB, kB, mp.DB, maxB)) return false;
-    if (pr.Ktotal <= 0 || round_up(pr.Ktotal, 1024) * maxA * maxB >= (int64_t(1) << 24)) return false;
+    // (a pooled sum adds four results before the conversion to an integer)
+    if (pr.Ktotal <= 0 || round_up(pr.Ktotal, 1024) * maxA * maxB * (mp.pool == 2 ? 4 : 1) >= (int64_t(1) << 24)) return false;
     if (pr.conv && mp.Cw % 2 != 0) return false;
     if (pr.conv && kA == OPK_PM1) kA = OPK_PM1Z;         // -1/+1 features: taps outside the frame must contribute 0
     mp.PA = pr.PA; mp.PB = pr.PB;
@@ -124,6 +125,8 @@ static int run_tile(const Problem &pr, TileParams &p, int vw, void *stream)
     bool use_xor = false;
     p.alpha = 1; p.uA = 0; p.uB = 0; p.c0 = 0;
     const bool a_pm = pr.encA == APNN_ENC_PM1, b_pm = pr.encB == APNN_ENC_PM1;
+    if (p.pool)
+        return fail(APNN_ERR_UNSUPPORTED, "%s: fused pooling needs the matrix-core path (Cin a multiple of 64, 4 K max|w| max|x| below 2^24)", pr.who);
     if (pr.conv && a_pm && (b_pm || p.pad > 0))
         return fail(APNN_ERR_UNSUPPORTED,
                     "%s: -1/+1 features in a convolution need the matrix-core path (Cin a multiple of 64, K below 2^24 / max|w|)",
@@ -173,6 +176,7 @@ static int run_either(const Problem &pr, TileParams &p, int vw, void *stream)
     mp.A = p.A; mp.B = p.B; mp.M = p.M; mp.N = p.N;
     mp.ldwA = p.ldwA; mp.ldwB = p.ldwB; mp.Kw = p.Kw;
     mp.H = p.H; mp.W = p.W; mp.Cw = p.Cw; mp.R = p.R; mp.S = p.S; mp.stride = p.stride; mp.pad = p.pad;
+    mp.pool = p.pool; mp.Hp = p.Hp; mp.Wp = p.Wp;
     mp.Ho = p.Ho; mp.Wo = p.Wo; mp.invCw = p.invCw;
     mp.Y = p.Y; mp.T = p.T; mp.scale = p.scale; mp.bias = p.bias;
     mp.res = p.res; mp.q_res = p.q_res; mp.res_scale = p.res_scale;
@@ -225,7 +229,11 @@ static int layer_impl(const char *who, const apnn_layer_desc &L, const uint32_t 
         Ho = static_cast<int>((d.H + 2 * d.pad - d.R) / d.stride + 1);
         Wo = static_cast<int>((d.W + 2 * d.pad - d.S) / d.stride + 1);
     }
-    const int64_t M = d.N * Ho * Wo, N = d.Cout;
+    if (L.pool != APNN_POOL_NONE && L.pool != APNN_POOL_MAX2 && L.pool != APNN_POOL_SUM2)
+        return fail(APNN_ERR_INVALID_ARG, "%s: pool = %d is not an apnn_pool value", who, L.pool);
+    if (L.pool && is_gemm) return fail(APNN_ERR_INVALID_ARG, "%s: pooling applies to convolutions only", who);
+    // with pooling the kernel enumerates 4 rows per pooled pixel (the grid), incomplete grids are dropped
+    const int64_t M = L.pool ? d.N * (Ho / 2) * (Wo / 2) * 4 : d.N * Ho * Wo, N = d.Cout;
     if (M > 0x7FFFFFFF || N > 0x7FFFFFFF || d.N * d.H * d.W > 0x7FFFFFFF)
         return fail(APNN_ERR_INVALID_ARG, "%s: dimension exceeds 2^31", who);
     if (M == 0 || N == 0) return APNN_OK;
@@ -249,6 +257,7 @@ static int layer_impl(const char *who, const apnn_layer_desc &L, const uint32_t 
         p.ldwA = 0; p.ldwB = p.Kw;
         p.H = static_cast<int>(d.H); p.W = static_cast<int>(d.W); p.R = d.R; p.S = d.S;
         p.stride = d.stride; p.pad = d.pad; p.Ho = Ho; p.Wo = Wo;
+        p.pool = L.pool; p.Hp = Ho / 2; p.Wp = Wo / 2;
         p.invCw = 1.0f / static_cast<float>(Cw);
         vw = (Cw % 4 == 0) ? 4 : (Cw % 2 == 0) ? 2 : 1;
     }

@@ -72,6 +72,10 @@ struct MfmaParams {
     // convolution geometry of the A operand (conv mode only)
     int H, W, Cw, R, S, stride, pad, Ho, Wo;
     float invCw;
+    // Fused 2 x 2 grid pooling (Sec. 5.2; convolution mode only): 0 none, 1 maximum, 2 sum.  Rows are then
+    // enumerated as 4 * (pooled pixel over N x Hp x Wp) + 2 dy + dx, so the four results of a grid are four
+    // consecutive accumulator registers of one lane; M counts these rows, the outputs have M / 4 rows.
+    int pool, Hp, Wp;
     // outputs, as in the AND+popcount kernel
     int32_t *Y;
     float *T;
@@ -171,6 +175,28 @@ __device__ __forceinline__ void finish_value(const MfmaParams &p, float v, int g
     }
 }
 
+// Row index of the convolution's implicit GEMM -> (image, output row, output column).
+__device__ __forceinline__ void conv_row_to_pixel(const MfmaParams &p, int gm, int &n, int &ho, int &wo)
+{
+    if (p.pool) {
+        const int P = gm >> 2, q = gm & 3;
+        const int wp = P % p.Wp, hp = (P / p.Wp) % p.Hp;
+        n = P / (p.Wp * p.Hp);
+        ho = 2 * hp + (q >> 1);
+        wo = 2 * wp + (q & 1);
+    } else {
+        wo = gm % p.Wo;
+        ho = (gm / p.Wo) % p.Ho;
+        n = gm / (p.Wo * p.Ho);
+    }
+}
+
+// The four results of a pooling grid (exact integers in fp32): maximum or sum.
+__device__ __forceinline__ float pool4(int mode, float a, float b, float c, float d)
+{
+    return mode == 1 ? fmaxf(fmaxf(a, b), fmaxf(c, d)) : (a + b) + (c + d);
+}
+
 template <int KIND> struct DigitPlanes { static constexpr int value = (KIND == OPK_U2 || KIND == OPK_PM1Z) ? 2 : 1; };
 
 template <int KA, int KB, int NWM, int NWN, int NSPLIT, int FM, int FN, int KC, int VW, bool CONV>
@@ -218,7 +244,8 @@ void mfma_fp4_kernel(const MfmaParams p)
 #pragma unroll
         for (int u = 0; u < A_SLOTS; ++u) {
             const int gm = m0 + (tid + NT * u) / (LA * CH);
-            const int wo = gm % p.Wo, ho = (gm / p.Wo) % p.Ho, n = gm / (p.Wo * p.Ho);
+            int wo, ho, n;
+            conv_row_to_pixel(p, gm, n, ho, wo);
             a_h0[u] = ho * p.stride - p.pad;
             a_w0[u] = wo * p.stride - p.pad;
             a_pix[u] = n * p.H * p.W;
@@ -322,7 +349,7 @@ void mfma_fp4_kernel(const MfmaParams p)
                 for (int rr = 0; rr < RPW; ++rr) {
                     const int gm = m0 + i * 32 + 8 * ks + 4 * lh + rr;     // accumulator register 4 ks + rr
                     uint32_t code = 0;
-                    if (p.res && gm < p.M && gn < p.N) {
+                    if (p.res && !p.pool && gm < p.M && gn < p.N) {
                         const uint32_t *rp = p.res + static_cast<int64_t>(gm) * p.q_res * p.NW + (gn >> 5);
                         for (int b = 0; b < p.q_res; ++b) code |= ((rp[b * p.NW] >> lr) & 1u) << b;
                     }
@@ -403,7 +430,7 @@ void mfma_fp4_kernel(const MfmaParams p)
     if constexpr (NSPLIT == 1) {
         constexpr int SLAB_STRIDE = BN + 4;                     // words; the pad keeps the two lane halves on different banks
         constexpr bool SLAB_FITS = NWM * 32 * SLAB_STRIDE <= TILE_WORDS;
-        if (SLAB_FITS && p.Y && !p.scale && (p.N & 3) == 0) {
+        if (SLAB_FITS && p.Y && !p.scale && (p.N & 3) == 0 && !p.pool) {
             // Plain int32 output: a lane's accumulators are 128-byte row fragments
             // scattered over 16 rows per tile.  They are transposed through LDS (one
             // slab of 32 rows per wave row at a time; the operand tiles are dead) so
@@ -430,15 +457,26 @@ void mfma_fp4_kernel(const MfmaParams p)
             return;
         }
         // compile-time indices keep the accumulators in registers
+        MfmaParams pq = p;                              // pooled outputs: a quarter of the rows, corrections per grid
+        pq.M = p.M >> 2;
+        pq.c0 = p.pool == 2 ? 4 * p.c0 : p.c0;
         static_for<FN>([&](auto jc) {
             constexpr int j = decltype(jc)::value;
             const int gn = n0 + wn * FN * 32 + j * 32 + lr;
             float sc = 0.0f, bi = 0.0f;
             if (p.scale && gn < p.N) { sc = p.scale[gn]; bi = p.bias[gn]; }
-            static_for<FM * 16>([&](auto irc) {
-                constexpr int i = decltype(irc)::value / 16, r = decltype(irc)::value % 16;
-                finish(acc[i][j][r], m0 + wm * FM * 32 + i * 32 + 8 * (r >> 2) + 4 * lh + (r & 3), gn, sc, bi, false, 0u);
-            });
+            if (p.pool) {
+                static_for<FM * 4>([&](auto ikc) {
+                    constexpr int i = decltype(ikc)::value / 4, k = decltype(ikc)::value % 4;
+                    const float v = pool4(p.pool, acc[i][j][4 * k], acc[i][j][4 * k + 1], acc[i][j][4 * k + 2], acc[i][j][4 * k + 3]);
+                    finish_value(pq, v, (m0 + wm * FM * 32 + i * 32 + 8 * k + 4 * lh) >> 2, gn, sc, bi, false, 0u, lr, lh);
+                });
+            } else {
+                static_for<FM * 16>([&](auto irc) {
+                    constexpr int i = decltype(irc)::value / 16, r = decltype(irc)::value % 16;
+                    finish(acc[i][j][r], m0 + wm * FM * 32 + i * 32 + 8 * (r >> 2) + 4 * lh + (r & 3), gn, sc, bi, false, 0u);
+                });
+            }
         });
     } else {
         // K-split block: the waves' partial tiles are added through LDS; wave ks then
@@ -453,6 +491,25 @@ void mfma_fp4_kernel(const MfmaParams p)
         static_for<FN>([&](auto jc) {
             constexpr int j = decltype(jc)::value;
             const int gn = n0 + j * 32 + lr;
+            if (p.pool) {                               // RPW = 4: the wave's registers of a tile are one pooling grid
+                static_assert(NSPLIT == 1 || RPW == 4, "a K-split wave finishes whole pooling grids");
+                MfmaParams pq = p;
+                pq.M = p.M >> 2;
+                pq.c0 = p.pool == 2 ? 4 * p.c0 : p.c0;
+                static_for<FM>([&](auto ic) {
+                    constexpr int i = decltype(ic)::value;
+                    float v4[4];
+#pragma unroll
+                    for (int rr = 0; rr < 4; ++rr) {
+                        v4[rr] = 0.0f;
+#pragma unroll
+                        for (int k = 0; k < NSPLIT; ++k) v4[rr] += sRed[k][(i * FN + j) * 16 + ks * 4 + rr][lane];
+                    }
+                    finish_value(pq, pool4(p.pool, v4[0], v4[1], v4[2], v4[3]), (m0 + i * 32 + 8 * ks + 4 * lh) >> 2, gn,
+                                 pre_sc[j], pre_bi[j], false, 0u, lr, lh);
+                });
+                return;
+            }
             static_for<FM * RPW>([&](auto irc) {
                 constexpr int i = decltype(irc)::value / RPW, rr = decltype(irc)::value % RPW;
                 const int r = ks * RPW + rr;

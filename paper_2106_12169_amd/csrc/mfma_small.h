@@ -58,7 +58,8 @@ __global__ __launch_bounds__(256) void mfma_small_kernel(const MfmaParams p)
     int a_h0 = 0, a_w0 = 0;
     int64_t a_pix = 0;
     if (CONV) {
-        const int wo = gmA % p.Wo, ho = (gmA / p.Wo) % p.Ho, n = gmA / (p.Wo * p.Ho);
+        int wo, ho, n;
+        conv_row_to_pixel(p, gmA, n, ho, wo);
         a_h0 = ho * p.stride - p.pad;
         a_w0 = wo * p.stride - p.pad;
         a_pix = static_cast<int64_t>(n) * p.H * p.W;
@@ -128,7 +129,7 @@ __global__ __launch_bounds__(256) void mfma_small_kernel(const MfmaParams p)
         const int r = ks * RPW + rr;
         const int gm = m0 + 8 * (r >> 2) + 4 * lh + (r & 3);
         uint32_t code = 0;
-        if (p.res && live && gm < p.M && gn < p.N) {
+        if (p.res && !p.pool && live && gm < p.M && gn < p.N) {
             const uint32_t *rp = p.res + static_cast<int64_t>(gm) * p.q_res * p.NW + (gn >> 5);
             for (int b = 0; b < p.q_res; ++b) code |= ((rp[b * p.NW] >> lr) & 1u) << b;
         }
@@ -190,8 +191,19 @@ __global__ __launch_bounds__(256) void mfma_small_kernel(const MfmaParams p)
         }
     }
 
+    MfmaParams pq = p;                          // pooled outputs: a quarter of the rows, corrections per grid
+    pq.M = p.M >> 2;
+    pq.c0 = p.pool == 2 ? 4 * p.c0 : p.c0;
     if constexpr (NSPLIT == 1) {
         if (!live) return;                      // wave-uniform: the ballots below stay whole-wave
+        if (p.pool) {                           // registers 4 k .. 4 k + 3 of a lane are one pooling grid
+            static_for<4>([&](auto kc) {
+                constexpr int k = decltype(kc)::value;
+                finish_value(pq, pool4(p.pool, acc[4 * k], acc[4 * k + 1], acc[4 * k + 2], acc[4 * k + 3]),
+                             (m0 + 8 * k + 4 * lh) >> 2, gn, sc, bi, false, 0u, lr, lh);
+            });
+            return;
+        }
         static_for<16>([&](auto rc) {
             constexpr int r = decltype(rc)::value;
             finish_value(p, acc[r], m0 + 8 * (r >> 2) + 4 * lh + (r & 3), gn, sc, bi, true, pre_res[r], lr, lh);
@@ -201,6 +213,18 @@ __global__ __launch_bounds__(256) void mfma_small_kernel(const MfmaParams p)
 #pragma unroll
         for (int r = 0; r < 16; ++r) sRed[ks][r][lane] = acc[r];
         __syncthreads();
+        if (p.pool) {                           // RPW = 4: this wave's share of the tile is one pooling grid per lane
+            static_assert(NSPLIT == 1 || RPW == 4, "a K-split wave finishes whole pooling grids");
+            float v4[4];
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+                v4[rr] = 0.0f;
+#pragma unroll
+                for (int k = 0; k < NSPLIT; ++k) v4[rr] += sRed[k][ks * 4 + rr][lane];
+            }
+            finish_value(pq, pool4(p.pool, v4[0], v4[1], v4[2], v4[3]), (m0 + 8 * ks + 4 * lh) >> 2, gn, sc, bi, false, 0u, lr, lh);
+            return;
+        }
 #pragma unroll
         for (int rr = 0; rr < RPW; ++rr) {
             const int r = ks * RPW + rr;

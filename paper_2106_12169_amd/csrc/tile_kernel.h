@@ -67,6 +67,7 @@ struct TileParams {
     int q_out;
     int NW;              // words per plane row of res/out: N / 32
     int xm, xn;          // 8 XCDs arranged as an xm x xn grid of tile regions (0: plain order)
+    int pool, Hp, Wp;    // fused 2 x 2 grid pooling request (matrix-core kernels only; this kernel has none)
 };
 
 // registers -> LDS in pieces of at most LV words (LDS rows are LV-word aligned)

@@ -80,10 +80,10 @@ def test_layer_validation():
 
     def layer(conv=d, **kw):
         args = dict(is_gemm=0, q_out=2, scale=FAKE, bias=FAKE, res=None, q_res=0, rs=0.0, acc=None, fo=None,
-                    W=FAKE, X=FAKE, out=FAKE)
+                    W=FAKE, X=FAKE, out=FAKE, pool=0)
         args.update(kw)
         desc = B.LayerDesc(conv.c(), args["is_gemm"], args["q_out"], args["scale"], args["bias"], args["res"],
-                           args["q_res"], args["rs"], args["acc"], args["fo"])
+                           args["q_res"], args["rs"], args["acc"], args["fo"], args["pool"])
         return _status(L.apnn_layer, C.byref(desc), args["W"], args["X"], args["out"], None)
 
     assert layer(conv=B.Conv(8, 28, 28, 100, 128, 3, 3, 1, 1))[0] == 1      # Cin not a multiple of 32
@@ -93,7 +93,10 @@ def test_layer_validation():
     assert layer(q_out=0)[0] == 1                                           # nothing requested
     assert layer(q_out=9)[0] == 2
     assert layer(res=FAKE, q_res=0)[0] == 2
-    assert layer(conv=B.Conv(8, 28, 28, 128, 128, 3, 3, 1, 1, encW=B.ENC_PM1, encX=B.ENC_PM1, q=1))[0] == 2
+    # -1/+1 features need the matrix-core form, which one channel word per tap does not allow
+    assert layer(conv=B.Conv(8, 28, 28, 32, 128, 3, 3, 1, 1, encW=B.ENC_PM1, encX=B.ENC_PM1, q=1))[0] == 2
+    assert layer(pool=3)[0] == 1                                            # not an apnn_pool value
+    assert layer(conv=B.Conv(8, 1, 1, 128, 128, 1, 1, 1, 0), is_gemm=1, pool=1)[0] == 1
     assert layer(conv=B.Conv(8, 2, 2, 128, 128, 7, 7, 1, 1))[0] == 1        # kernel larger than padded frame
     assert layer(is_gemm=1)[0] == 1                                         # gemm layer with H = 28
     assert layer(conv=B.Conv(0, 28, 28, 128, 128, 3, 3, 1, 1))[0] == 0      # empty batch

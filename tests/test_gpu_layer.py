@@ -290,3 +290,60 @@ def test_patch_packer_geometries(C, H, W, R, S, stride, pad, bits):
     # pad words of the operand (kernel rows beyond R) are zero
     words = hp.words_u32(Xp).reshape(BS * Ho * Wo, bits, -1)
     assert (words[:, :, R:] == 0).all()
+
+
+@pytest.mark.parametrize("force", ["auto", "64", "32split1", "32split4"])
+@pytest.mark.parametrize("mode", [B.POOL_MAX2, B.POOL_SUM2])
+@pytest.mark.parametrize("BS,Cin,Cout,H,Wd,R,stride,pad,with_res", [
+    (2, 64, 64, 14, 14, 3, 1, 1, False),
+    (1, 128, 96, 9, 11, 3, 1, 1, True),        # odd output frame: the last row and column of results are dropped
+    (2, 64, 32, 12, 12, 1, 1, 0, False),       # 1 x 1
+    (1, 64, 64, 56, 56, 3, 1, 1, True),        # enough rows for the 64 x 64 block tile
+])
+def test_fused_pooling_matches_oracle(monkeypatch, force, mode, BS, Cin, Cout, H, Wd, R, stride, pad, with_res):
+    """conv -> 2 x 2 grid pooling of the int32 results -> scale/bias (+ residual) -> requantise -> repack, one kernel."""
+    for v in ("APNN_TILE", "APNN_MFMA", "APNN_MFMA_TILE", "APNN_MFMA_SMALL", "APNN_MFMA_NSPLIT"):
+        monkeypatch.delenv(v, raising=False)
+    if force != "auto":
+        monkeypatch.setenv("APNN_MFMA_TILE", force[:2])
+        if force.startswith("32split"):
+            monkeypatch.setenv("APNN_MFMA_NSPLIT", force[-1])
+    Wv = wl.fair_signs(71 + Cin, (Cout, Cin, R, R))
+    Xv = wl.uniform_codes(72 + H, (BS, Cin, H, Wd), 2)
+    d = B.Conv(BS, H, Wd, Cin, Cout, R, R, stride, pad, 1, 2, P, U)
+    Hp, Wp = d.Ho // 2, d.Wo // 2
+    K = Cin * R * R
+    div = np.sqrt(K * 3.5) * (4.0 if mode == B.POOL_SUM2 else 1.0)
+    scale = (wl.normals(73, (Cout,), 1.0, 0.2) / div).astype(np.float32)
+    bias = wl.normals(74, (Cout,), 1.0 if mode == B.POOL_MAX2 else 2.0, 0.3)
+    res = wl.uniform_codes(75, (BS, Cout, Hp, Wp), 2) if with_res else None
+    resp = B.apnn_pack_fmap(dev(res), B.LAYOUT_NCHW, 2, U) if with_res else None
+    acc = torch.empty((BS, Hp, Wp, Cout), dtype=torch.int32, device="cuda")
+    tf = torch.empty((BS, Hp, Wp, Cout), dtype=torch.float32, device="cuda")
+    out = B.apnn_layer(d, B.apnn_pack_conv_weights(dev(Wv), 1, P), B.apnn_pack_fmap(dev(Xv), B.LAYOUT_NCHW, 2, U),
+                       q_out=2, scale=dev(scale), bias=dev(bias), residual=resp, q_res=2, res_scale=0.5,
+                       acc_out=acc, float_out=tf, pool=mode)
+    torch.cuda.synchronize()
+    pooled = oracle.gridpool(oracle.conv2d(Wv, P, 1, Xv, U, 2, stride, pad), 2, oracle.POOL_MAX if mode == B.POOL_MAX2 else oracle.POOL_SUM)
+    want_codes, want_t = oracle.epilogue(pooled, scale, bias, 2, res=res, res_scale=0.5, want_t=True)
+    assert np.array_equal(acc.cpu().numpy().transpose(0, 3, 1, 2), pooled)
+    assert np.array_equal(tf.cpu().numpy().transpose(0, 3, 1, 2), want_t)
+    codes, pad_bits = hp.unpack_fmap(hp.words_u32(out), BS, Hp, Wp, Cout, 2)
+    assert np.array_equal(codes, want_codes) and pad_bits == 0
+    assert len(np.unique(want_codes)) == 4
+
+
+def test_fused_pooling_refusals(monkeypatch):
+    e = torch.zeros(1 << 16, dtype=torch.int32, device="cuda")
+    f = torch.zeros(64, dtype=torch.float32, device="cuda")
+    d = B.Conv(1, 8, 8, 64, 64, 3, 3, 1, 1, 1, 2, P, U)
+    with pytest.raises(B.ApnnError) as ei:                      # not an apnn_pool value
+        B.apnn_layer(d, e, e, q_out=2, scale=f, bias=f, pool=3)
+    assert ei.value.status == 1
+    with pytest.raises(B.ApnnError) as ei:                      # GEMM layers have no frame to pool
+        B.apnn_layer(B.Conv(8, 1, 1, 64, 64, 1, 1, 1, 0, 1, 2, P, U), e, e, is_gemm=True, q_out=2, scale=f, bias=f, pool=1)
+    assert ei.value.status == 1
+    monkeypatch.setenv("APNN_MFMA", "0")                        # the AND+popcount kernel does not pool
+    with pytest.raises(B.ApnnError) as ei:
+        B.apnn_layer(d, e, e, q_out=2, scale=f, bias=f, pool=1)
+    assert ei.value.status == 2
