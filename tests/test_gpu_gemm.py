@@ -139,3 +139,21 @@ def test_paper_fc_shapes(w, a, dim):
     wk = wl.paper_fc_workload(w, a, dim)
     W, X = wk.weights(), wk.activations()
     assert np.array_equal(gpu_gemm(W, U, w, X, U, a), oracle.gemm(W, U, w, X, U, a))
+
+
+@pytest.mark.parametrize("encW,p,encX,q,K", [
+    (U, 3, U, 5, 4096),            # 2 x 3 base-4 digit passes, weights of Eq. 1 carried by the instruction's block scales
+    (P, 1, P, 1, 4096 + 40),       # Case II on the large-tile kernel, K pad correction
+    (U, 2, P, 1, 2000),            # mirrored Case III, ragged K
+])
+def test_large_tile_kernel_full_width_sampled(encW, p, encX, q, K):
+    """M = N = 4096 (256 tiles of 256 x 256, the launch shape of the headline benchmark) for other digit kinds:
+    sampled rows against the oracle plus the column-sum identity over every output."""
+    M = N = 4096
+    W = wl.operand(900 + p + K, M, K, p, encW)
+    X = wl.operand(901 + q + K, N, K, q, encX)
+    Y = gpu_gemm(W, encW, p, X, encX, q)
+    rows = np.unique(np.concatenate([[0, 255, 256, 4095], (wl.raw_u64(7, 0, 12) % np.uint64(M)).astype(int)]))
+    assert np.array_equal(Y[rows], oracle.gemm(W[rows], encW, p, X, encX, q))
+    colw = W.astype(np.int64).sum(0)
+    assert np.array_equal(Y.astype(np.int64).sum(0), X.astype(np.int64) @ colw)
