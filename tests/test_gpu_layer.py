@@ -347,3 +347,35 @@ def test_fused_pooling_refusals(monkeypatch):
     with pytest.raises(B.ApnnError) as ei:
         B.apnn_layer(d, e, e, q_out=2, scale=f, bias=f, pool=1)
     assert ei.value.status == 2
+
+
+@pytest.mark.parametrize("force", ["256", "128", "64", "auto"])
+@pytest.mark.parametrize("q,q_out,with_res", [(2, 2, True), (4, 3, False), (1, 1, False)])
+def test_fused_gemm_layer_all_matrix_tiles(monkeypatch, force, q, q_out, with_res):
+    """Fully-connected layer with the whole epilogue (scale/bias, residual, requantise, repack, int32 and fp32 side
+    outputs) through every matrix-operand kernel, the large-tile one included; ragged batch."""
+    for v in ("APNN_TILE", "APNN_MFMA", "APNN_MFMA_TILE", "APNN_MFMA_SMALL", "APNN_MFMA_NSPLIT"):
+        monkeypatch.delenv(v, raising=False)
+    if force != "auto":
+        monkeypatch.setenv("APNN_MFMA_TILE", force)
+    BS, K, Cout = 600, 1000, 320
+    Xv = wl.uniform_codes(81 + q, (BS, K), q)
+    Wv = wl.fair_signs(82, (Cout, K))
+    scale = (wl.normals(83, (Cout,), 1.0, 0.2) / np.sqrt(K * ((1 << q) ** 2) / 4.0)).astype(np.float32)
+    bias = wl.normals(84, (Cout,), 0.5 * (1 << q_out), 0.3)
+    res = wl.uniform_codes(85, (BS, Cout), 2) if with_res else None
+    d = B.Conv(BS, 1, 1, K, Cout, 1, 1, 1, 0, 1, q, P, U)
+    acc = torch.empty((BS, Cout), dtype=torch.int32, device="cuda")
+    tf = torch.empty((BS, Cout), dtype=torch.float32, device="cuda")
+    out = B.apnn_layer(d, B.apnn_pack(dev(Wv), 1, P), B.apnn_pack(dev(Xv), q, U), is_gemm=True, q_out=q_out,
+                       scale=dev(scale), bias=dev(bias),
+                       residual=B.apnn_pack_fmap(dev(res.reshape(BS, Cout, 1, 1)), B.LAYOUT_NCHW, 2, U) if with_res else None,
+                       q_res=2, res_scale=0.5, acc_out=acc, float_out=tf)
+    torch.cuda.synchronize()
+    want_acc = oracle.gemm(Xv, U, q, Wv, P, 1)
+    want_codes, want_t = oracle.epilogue(want_acc, scale, bias, q_out, res=res, res_scale=0.5, want_t=True)
+    assert np.array_equal(acc.cpu().numpy(), want_acc)
+    assert np.array_equal(tf.cpu().numpy(), want_t)
+    codes, pad_bits = hp.unpack_fmap(hp.words_u32(out), BS, 1, 1, Cout, q_out)
+    assert np.array_equal(codes.reshape(BS, Cout), want_codes) and pad_bits == 0
+    assert len(np.unique(want_codes)) == (1 << q_out)
