@@ -84,7 +84,8 @@ static bool try_mfma(const Problem &pr, MfmaParams &mp, void *stream, int &rc)
         const int64_t lim = int64_t(1) << 31;
         if (4 * pr.M * pr.PA * mp.ldwA >= lim || 4 * pr.N * pr.PB * mp.ldwB >= lim || 4 * (pr.M + 256) * pr.N >= lim) t = 128;
     }
-    const bool short_k = !pr.conv && mp.Kw <= 8 && t <= 64;      // 8-word chunks: no step multiplies padding
+    const char *esk = std::getenv("APNN_MFMA_SHORTK");           // 0: no special case for short K (experiments)
+    const bool short_k = !pr.conv && mp.Kw <= 8 && t <= 64 && !(esk && std::atoi(esk) == 0);   // 8-word chunks: no step multiplies padding
     if (short_k) t = 64;
     const int kc = short_k ? 8 : mfma_chunk_words(t);
     mp.nk = static_cast<int>(ceil_div(mp.Kw, kc));

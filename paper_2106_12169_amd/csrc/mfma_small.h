@@ -136,35 +136,28 @@ __global__ __launch_bounds__(256) void mfma_small_kernel(const MfmaParams p)
         pre_res[rr] = code;
     }
 
-    // digit pairs diagonal by diagonal, Horner evaluation in base 4 (as in mfma_fp4_kernel)
-    const int dmax = p.DA + p.DB - 2;
-    auto first_a = [&](int d) { return max(0, d - (p.DB - 1)); };
-    auto next_pair = [&](int &a_, int &b_) {
-        if (a_ + 1 < p.DA && b_ - 1 >= 0) { ++a_; --b_; return false; }
-        const int d = a_ + b_ - 1;
-        if (d < 0) return false;
-        a_ = first_a(d); b_ = d - a_;
-        return true;
-    };
-    const int npairs = p.Kw > 0 ? p.DA * p.DB : 0;
-    int da = first_a(dmax), db = dmax - da;
+    // Digit pairs (da, db) and the groups of four steps of each are walked as one
+    // flat sequence, GMAX entries at a time with all their loads in flight together,
+    // so that a multi-digit layer (e.g. 8-bit features: four passes) pays one memory
+    // round trip, not one per pass.  The weight 4^(da + db) of a pair (Eq. 1) enters
+    // as the block scales of the matrix instruction, which makes the order free.
+    const int total = p.Kw > 0 ? p.DA * p.DB * G : 0;
+    const int kbase = lh * NSe + ks * G * 4;            // first K word of this lane's steps
 
     v16f_t acc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
 
-    for (int pair = 0; pair < npairs; ++pair) {
-        const int planeA = LA == 2 ? 2 * da : da, planeB = LB == 2 ? 2 * db : db;
-        const int kbase = lh * NSe + ks * G * 4;        // first K word of this lane's steps
-        for (int g0 = 0; g0 < G; g0 += GMAX) {
+    if (p.DA * p.DB == 1) {                             // one digit pair (most layers): unit scales, plain group loop
+        for (int g0 = 0; g0 < (p.Kw > 0 ? G : 0); g0 += GMAX) {
             uint4 wa[GMAX][LA], wb[GMAX][LB];
 #pragma unroll
             for (int g = 0; g < GMAX; ++g) {
                 const int kk = (g0 + g < G) ? kbase + 4 * (g0 + g) : p.Kw;       // beyond G: reads as zero, not used
 #pragma unroll
-                for (int pl = 0; pl < LA; ++pl) wa[g][pl] = load_a(planeA + pl, kk);
+                for (int pl = 0; pl < LA; ++pl) wa[g][pl] = load_a(pl, kk);
 #pragma unroll
-                for (int pl = 0; pl < LB; ++pl) wb[g][pl] = load_b(planeB + pl, kk);
+                for (int pl = 0; pl < LB; ++pl) wb[g][pl] = load_b(pl, kk);
             }
 #pragma unroll
             for (int g = 0; g < GMAX; ++g) {
@@ -184,10 +177,44 @@ __global__ __launch_bounds__(256) void mfma_small_kernel(const MfmaParams p)
                 }
             }
         }
-        const bool new_diag = next_pair(da, db);
-        if (new_diag && pair + 1 < npairs) {
+    }
+    int da = 0, db = 0, grp = 0;                        // position in the flat sequence (scalar counters, no divisions)
+    for (int e0 = 0; e0 < (p.DA * p.DB == 1 ? 0 : total); e0 += GMAX) {
+        uint4 wa[GMAX][LA], wb[GMAX][LB];
+        int sa[GMAX], sb[GMAX];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[r] *= 4.0f;
+        for (int g = 0; g < GMAX; ++g) {
+            const int planeA = LA == 2 ? 2 * da : da, planeB = LB == 2 ? 2 * db : db;
+            const int kk = e0 + g < total ? kbase + 4 * grp : p.Kw;             // beyond the end: reads as zero, not used
+            sa[g] = 0x7f7f7f7f + 0x02020202 * da;
+            sb[g] = 0x7f7f7f7f + 0x02020202 * db;
+#pragma unroll
+            for (int pl = 0; pl < LA; ++pl) wa[g][pl] = load_a(planeA + pl, kk);
+#pragma unroll
+            for (int pl = 0; pl < LB; ++pl) wb[g][pl] = load_b(planeB + pl, kk);
+            ++grp;                                      // next group, then next digit of B, then next digit of A
+            const bool wg = grp == G;
+            grp = wg ? 0 : grp;
+            db += wg ? 1 : 0;
+            const bool wd = db == p.DB;
+            db = wd ? 0 : db;
+            da += wd ? 1 : 0;
+        }
+#pragma unroll
+        for (int g = 0; g < GMAX; ++g) {
+            if (e0 + g < total) {
+                const uint32_t a0[4] = {wa[g][0].x, wa[g][0].y, wa[g][0].z, wa[g][0].w};
+                const uint32_t a1[4] = {wa[g][LA - 1].x, wa[g][LA - 1].y, wa[g][LA - 1].z, wa[g][LA - 1].w};
+                const uint32_t b0[4] = {wb[g][0].x, wb[g][0].y, wb[g][0].z, wb[g][0].w};
+                const uint32_t b1[4] = {wb[g][LB - 1].x, wb[g][LB - 1].y, wb[g][LB - 1].z, wb[g][LB - 1].w};
+#pragma unroll
+                for (int st = 0; st < 4; ++st) {
+                    v8i_t fa, fb;
+                    expand_fp4<KA>(a0[st], a1[st], km, fa);
+                    expand_fp4<KB>(b0[st], b1[st], km, fb);
+                    acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fa, fb, acc, 4, 4, 0, sa[g], 0, sb[g]);
+                }
+            }
         }
     }
 
