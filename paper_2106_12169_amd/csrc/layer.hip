@@ -99,7 +99,7 @@ static bool try_mfma(const Problem &pr, MfmaParams &mp, void *stream, int &rc)
         const char *en = std::getenv("APNN_MFMA_NSPLIT");
         int nsplit = tiles <= 4096 ? 4 : 1;                            // measured: the split wins up to a few thousand tiles
         if (en && (std::atoi(en) == 1 || std::atoi(en) == 4)) nsplit = std::atoi(en);
-        const int64_t nse = round_up(ceil_div(mp.Kw, 2), 4 * nsplit);
+        const int64_t nse = round_up(ceil_div(mp.Kw, 2), 4);          // steps of the small-layer kernel (groups of four)
         mp.nk = 1;
         mp.c0 = (kA == OPK_PM1 && kB == OPK_PM1) ? -static_cast<int>(nse * 64 - pr.Ktotal) : 0;
         const unsigned g = static_cast<unsigned>(nsplit == 1 ? ceil_div(tiles, 4) : tiles);

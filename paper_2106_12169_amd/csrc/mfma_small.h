@@ -16,8 +16,8 @@
 // epilogue are those of mfma_fp4_kernel.
 //
 // Step geometry (run time): ceil(Kw / 2) steps would do; that is rounded up to
-// NSe, a multiple of 4 * NSPLIT, so that every wave owns whole groups of four
-// steps.  Lane-half h of step s takes K word h*NSe + s (any pairing of K
+// NSe, a multiple of 4: groups of four steps, dealt to the NSPLIT waves of a block
+// in turn.  Lane-half h of step s takes K word h*NSe + s (any pairing of K
 // positions with steps is valid as long as both operands use the same one);
 // words at and beyond Kw read as zero.
 #pragma once
@@ -45,8 +45,9 @@ __global__ __launch_bounds__(256) void mfma_small_kernel(const MfmaParams p)
     const bool live = tile < tilesM * tilesN;           // trailing waves of the last block have no tile
     const int m0 = (tile / tilesN) * 32, n0 = (tile % tilesN) * 32;
 
-    const int NSe = (((p.Kw + 1) >> 1) + 4 * NSPLIT - 1) / (4 * NSPLIT) * (4 * NSPLIT);
-    const int G = NSe / (4 * NSPLIT);                   // groups of four steps of this wave
+    const int NSe = (((p.Kw + 1) >> 1) + 3) / 4 * 4;
+    const int GT = NSe / 4;                             // groups of four steps in all; wave ks takes groups ks, ks + NSPLIT, ...
+    const int G = (GT - ks + NSPLIT - 1) / NSPLIT;      // ... of which this wave has G (waves of a block may differ by one)
 
     Fp4Masks km;
     km.m1 = reg_const(0x11111111u); km.m2 = reg_const(0x22222222u);
@@ -142,7 +143,7 @@ __global__ __launch_bounds__(256) void mfma_small_kernel(const MfmaParams p)
     // round trip, not one per pass.  The weight 4^(da + db) of a pair (Eq. 1) enters
     // as the block scales of the matrix instruction, which makes the order free.
     const int total = p.Kw > 0 ? p.DA * p.DB * G : 0;
-    const int kbase = lh * NSe + ks * G * 4;            // first K word of this lane's steps
+    const int kbase = lh * NSe + 4 * ks;                // first K word of this lane's first group; the next is 4 NSPLIT further
 
     v16f_t acc;
 #pragma unroll
@@ -153,7 +154,7 @@ __global__ __launch_bounds__(256) void mfma_small_kernel(const MfmaParams p)
             uint4 wa[GMAX][LA], wb[GMAX][LB];
 #pragma unroll
             for (int g = 0; g < GMAX; ++g) {
-                const int kk = (g0 + g < G) ? kbase + 4 * (g0 + g) : p.Kw;       // beyond G: reads as zero, not used
+                const int kk = (g0 + g < G) ? kbase + 4 * NSPLIT * (g0 + g) : p.Kw;   // beyond G: reads as zero, not used
 #pragma unroll
                 for (int pl = 0; pl < LA; ++pl) wa[g][pl] = load_a(pl, kk);
 #pragma unroll
@@ -185,7 +186,7 @@ __global__ __launch_bounds__(256) void mfma_small_kernel(const MfmaParams p)
 #pragma unroll
         for (int g = 0; g < GMAX; ++g) {
             const int planeA = LA == 2 ? 2 * da : da, planeB = LB == 2 ? 2 * db : db;
-            const int kk = e0 + g < total ? kbase + 4 * grp : p.Kw;             // beyond the end: reads as zero, not used
+            const int kk = e0 + g < total ? kbase + 4 * NSPLIT * grp : p.Kw;    // beyond the end: reads as zero, not used
             sa[g] = 0x7f7f7f7f + 0x02020202 * da;
             sb[g] = 0x7f7f7f7f + 0x02020202 * db;
 #pragma unroll
