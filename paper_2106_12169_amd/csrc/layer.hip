@@ -178,6 +178,14 @@ static int run_either(const Problem &pr, TileParams &p, int vw, void *stream)
     mp.ldwA = p.ldwA; mp.ldwB = p.ldwB; mp.Kw = p.Kw;
     mp.H = p.H; mp.W = p.W; mp.Cw = p.Cw; mp.R = p.R; mp.S = p.S; mp.stride = p.stride; mp.pad = p.pad;
     mp.pool = p.pool; mp.Hp = p.Hp; mp.Wp = p.Wp;
+    if (pr.conv) {
+        mp.invS = 1.0f / static_cast<float>(p.S);
+        mp.invWo = 1.0f / static_cast<float>(p.Wo);
+        mp.invHoWo = 1.0f / (static_cast<float>(p.Ho) * static_cast<float>(p.Wo));
+        mp.invWp = 1.0f / static_cast<float>(p.Wp > 0 ? p.Wp : 1);
+        mp.invHpWp = 1.0f / (static_cast<float>(p.Hp > 0 ? p.Hp : 1) * static_cast<float>(p.Wp > 0 ? p.Wp : 1));
+        mp.fastdiv = (pr.M + 256 < (int64_t(1) << 21)) ? 1 : 0;      // row indices, tile overhang included, stay below 2^21
+    }
     mp.Ho = p.Ho; mp.Wo = p.Wo; mp.invCw = p.invCw;
     mp.Y = p.Y; mp.T = p.T; mp.scale = p.scale; mp.bias = p.bias;
     mp.res = p.res; mp.q_res = p.q_res; mp.res_scale = p.res_scale;

@@ -76,6 +76,10 @@ struct MfmaParams {
     // enumerated as 4 * (pooled pixel over N x Hp x Wp) + 2 dy + dx, so the four results of a grid are four
     // consecutive accumulator registers of one lane; M counts these rows, the outputs have M / 4 rows.
     int pool, Hp, Wp;
+    // Reciprocals for the index arithmetic of the convolution loader: floor(n / d) = int((n + 0.5f) * (1 / d)) is
+    // exact for n < 2^21, which the host checks (fastdiv); larger problems divide integers.
+    float invS, invWo, invHoWo, invWp, invHpWp;
+    int fastdiv;
     // outputs, as in the AND+popcount kernel
     int32_t *Y;
     float *T;
@@ -175,20 +179,41 @@ __device__ __forceinline__ void finish_value(const MfmaParams &p, float v, int g
     }
 }
 
+__device__ __forceinline__ int div_by_reciprocal(int n, float inv)
+{
+    return static_cast<int>((static_cast<float>(n) + 0.5f) * inv);
+}
+
 // Row index of the convolution's implicit GEMM -> (image, output row, output column).
 __device__ __forceinline__ void conv_row_to_pixel(const MfmaParams &p, int gm, int &n, int &ho, int &wo)
 {
-    if (p.pool) {
-        const int P = gm >> 2, q = gm & 3;
-        const int wp = P % p.Wp, hp = (P / p.Wp) % p.Hp;
-        n = P / (p.Wp * p.Hp);
-        ho = 2 * hp + (q >> 1);
-        wo = 2 * wp + (q & 1);
+    const int P = p.pool ? gm >> 2 : gm;                // (pooled) pixel in raster order over N x Hq x Wq
+    const int Wq = p.pool ? p.Wp : p.Wo, Hq = p.pool ? p.Hp : p.Ho;
+    int row, col;                                       // P = (n * Hq + row) * Wq + col
+    if (p.fastdiv) {
+        const int q = div_by_reciprocal(P, p.pool ? p.invWp : p.invWo);
+        col = P - q * Wq;
+        n = div_by_reciprocal(P, p.pool ? p.invHpWp : p.invHoWo);
+        row = q - n * Hq;
     } else {
-        wo = gm % p.Wo;
-        ho = (gm / p.Wo) % p.Ho;
-        n = gm / (p.Wo * p.Ho);
+        col = P % Wq;
+        row = (P / Wq) % Hq;
+        n = P / (Wq * Hq);
     }
+    if (p.pool) {
+        ho = 2 * row + ((gm >> 1) & 1);
+        wo = 2 * col + (gm & 1);
+    } else {
+        ho = row;
+        wo = col;
+    }
+}
+
+// Tap index -> (kernel row, kernel column).
+__device__ __forceinline__ void tap_to_rs(const MfmaParams &p, int tap, int &r, int &sc)
+{
+    r = div_by_reciprocal(tap, p.invS);                 // tap < R S, far below the exactness limit
+    sc = tap - r * p.S;
 }
 
 // The four results of a pooling grid (exact integers in fp32): maximum or sum.
@@ -265,7 +290,8 @@ void mfma_fp4_kernel(const MfmaParams p)
                 if (CONV) {
                     const int tap = static_cast<int>((static_cast<float>(kk) + 0.5f) * p.invCw);
                     const int cw = kk - tap * p.Cw;
-                    const int r = tap / p.S, sc = tap - r * p.S;
+                    int r, sc;
+                    tap_to_rs(p, tap, r, sc);
                     const int h = a_h0[u] + r, w = a_w0[u] + sc;
                     if (h >= 0 && h < p.H && w >= 0 && w < p.W) {
                         const int64_t pix = a_pix[u] + h * p.W + w;

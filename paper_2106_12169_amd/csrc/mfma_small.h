@@ -82,7 +82,8 @@ __global__ __launch_bounds__(256) void mfma_small_kernel(const MfmaParams p)
                 if (k < p.Kw) {
                     const int tap = static_cast<int>((static_cast<float>(k) + 0.5f) * p.invCw);
                     const int cw = k - tap * p.Cw;
-                    const int r = tap / p.S, sc = tap - r * p.S;
+                    int r, sc;
+                    tap_to_rs(p, tap, r, sc);
                     const int h = a_h0 + r, w = a_w0 + sc;
                     if (h >= 0 && h < p.H && w >= 0 && w < p.W) {
                         const uint32_t *src = p.A + ((a_pix + h * p.W + w) * p.PA + plane) * p.Cw + cw;
