@@ -57,7 +57,7 @@ static int pick_mfma_tile(int64_t M, int64_t N, bool conv)
     // wastes at most a quarter of its area on the ragged edges
     auto tiles = [&](int t) { return ceil_div(M, t) * ceil_div(N, t); };
     auto useful = [&](int t) { return static_cast<double>(M) * N / (static_cast<double>(tiles(t)) * t * t); };
-    if (!conv && tiles(256) >= 128 && useful(256) >= 0.75) return 256;
+    if (!conv && tiles(256) >= 192 && useful(256) >= 0.75) return 256;
     if (tiles(128) >= 192 && useful(128) >= 0.75) return 128;
     if (tiles(64) >= 1024) return 64;
     return 32;                                  // small layers: one wave tile per block, K split over its waves
@@ -80,9 +80,9 @@ static bool try_mfma(const Problem &pr, MfmaParams &mp, void *stream, int &rc)
     // 0 pad bits of two -1/+1 operands multiply to +1 at every padded K position
     int t = pick_mfma_tile(pr.M, pr.N, pr.conv);
     if (kA == OPK_PM1Z && t == 128) t = 64;              // instantiated for the 64-tile and the small-layer kernel
-    if (t == 256) {                             // that kernel addresses operands and output with 31-bit byte offsets
+    if ((t == 256 || t == 128) && !pr.conv) {   // the pipelined kernel addresses operands and output with 31-bit byte offsets
         const int64_t lim = int64_t(1) << 31;
-        if (4 * pr.M * pr.PA * mp.ldwA >= lim || 4 * pr.N * pr.PB * mp.ldwB >= lim || 4 * (pr.M + 256) * pr.N >= lim) t = 128;
+        if (4 * pr.M * pr.PA * mp.ldwA >= lim || 4 * pr.N * pr.PB * mp.ldwB >= lim || 4 * (pr.M + 256) * pr.N >= lim) t = 64;
     }
     const char *esk = std::getenv("APNN_MFMA_SHORTK");           // 0: no special case for short K (experiments)
     const bool short_k = !pr.conv && mp.Kw <= 8 && t <= 64 && !(esk && std::atoi(esk) == 0);   // 8-word chunks: no step multiplies padding

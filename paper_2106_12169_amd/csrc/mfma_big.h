@@ -135,7 +135,7 @@ __device__ __forceinline__ void expand_task(uint32_t x0, uint32_t x1, const Pair
 }
 
 template <int KA, int KB, int NWM, int NWN, int FM, int FN>
-__global__ __launch_bounds__(64 * NWM * NWN, 1) void mfma_big_kernel(const MfmaParams p)
+__global__ __launch_bounds__(64 * NWM * NWN, FM * FN >= 16 ? 1 : 2) void mfma_big_kernel(const MfmaParams p)
 {
     constexpr int KC = 16;                              // words per chunk = 8 matrix-instruction steps = 2 groups of 4
     constexpr int LA = DigitPlanes<KA>::value, LB = DigitPlanes<KB>::value;
@@ -261,7 +261,17 @@ __global__ __launch_bounds__(64 * NWM * NWN, 1) void mfma_big_kernel(const MfmaP
     //   even step 2 k:      expand A and B of step 2 k + 1, prep A (pair k + 1)
     constexpr int NMI = FM * FN;
     constexpr int EA = KA == OPK_U2 ? 2 : 1, EB = KB == OPK_U2 ? 2 : 1;            // expansion tasks per fragment row
-    static_assert(NREAD <= NMI && A_SLOTS + B_SLOTS <= NMI, "at most one memory instruction of each kind per portion");
+    constexpr int NLOAD = A_SLOTS + B_SLOTS;
+    // memory instructions are dealt to the portions of a step like the tasks: portion q takes reads / loads
+    // [N q / NMI, N (q + 1) / NMI)
+    auto reads_of = [&](int buf, auto gc, auto qc, uint4 (&wa)[FM][LA], uint4 (&wb)[FN][LB]) {
+        constexpr int q = decltype(qc)::value, lo = NREAD * q / NMI, hi = NREAD * (q + 1) / NMI;
+        static_for<hi - lo>([&](auto ic) { read_one(buf, gc, std::integral_constant<int, lo + decltype(ic)::value>{}, wa, wb); });
+    };
+    auto loads_of = [&](const FetchState &fs, int buf, auto qc) {
+        constexpr int q = decltype(qc)::value, lo = NLOAD * q / NMI, hi = NLOAD * (q + 1) / NMI;
+        static_for<hi - lo>([&](auto ic) { fetch_one(fs, buf, std::integral_constant<int, lo + decltype(ic)::value>{}); });
+    };
     PairPrep ppa[FM], ppb[FN];
     PairTmp tta[FM], ttb[FN];
     // ODD: parity of the step being multiplied.  xw*/XST: group words and index (0..3) of the step to expand;
@@ -376,7 +386,7 @@ __global__ __launch_bounds__(64 * NWM * NWN, 1) void mfma_big_kernel(const MfmaP
         asm volatile("" : "+v"(sa), "+v"(sb));          // in vector registers before the first portion
         __builtin_amdgcn_sched_barrier(0);
         //   multiply step | expand step (words, index) into | prepare pair (words, which) | memory
-        step(I0{}, ea0, eb0, sa, sb, wa0, wb0, I1{}, ea1, eb1, wa0, wb0, I1{}, [&](auto qc) { read_one(buf, I1{}, qc, wa1, wb1); });
+        step(I0{}, ea0, eb0, sa, sb, wa0, wb0, I1{}, ea1, eb1, wa0, wb0, I1{}, [&](auto qc) { reads_of(buf, I1{}, qc, wa1, wb1); });
         step(I1{}, ea1, eb1, sa, sb, wa0, wb0, I2{}, ea0, eb0, wa0, wb0, I1{}, no_hook);
         step(I0{}, ea0, eb0, sa, sb, wa0, wb0, I3{}, ea1, eb1, wa1, wb1, I0{}, no_hook);
         step(I1{}, ea1, eb1, sa, sb, wa1, wb1, I0{}, ea0, eb0, wa1, wb1, I0{}, no_hook);
@@ -388,8 +398,8 @@ __global__ __launch_bounds__(64 * NWM * NWN, 1) void mfma_big_kernel(const MfmaP
         advance(fda, fdb, fk);
         __builtin_amdgcn_sched_barrier(0);
         step(I0{}, ea0, eb0, sa, sb, wa1, wb1, I3{}, ea1, eb1, wa0, wb0, I0{}, [&](auto qc) {
-            read_one(buf ^ 1, I0{}, qc, wa0, wb0);      // (the A reads come first; prep A of this step, last, uses them)
-            fetch_one(fs, buf, qc);
+            reads_of(buf ^ 1, I0{}, qc, wa0, wb0);      // (the A reads come first; prep A of this step, last, uses them)
+            loads_of(fs, buf, qc);
         });
         step(I1{}, ea1, eb1, sa, sb, wa0, wb0, I0{}, ea0, eb0, wa0, wb0, I0{}, no_hook);
         advance(cda, cdb, ck);
