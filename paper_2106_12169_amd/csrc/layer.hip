@@ -103,7 +103,8 @@ static bool try_mfma(const Problem &pr, MfmaParams &mp, void *stream, int &rc)
         mp.nk = 1;
         mp.c0 = (kA == OPK_PM1 && kB == OPK_PM1) ? -static_cast<int>(nse * 64 - pr.Ktotal) : 0;
         const unsigned g = static_cast<unsigned>(nsplit == 1 ? ceil_div(tiles, 4) : tiles);
-        ok = pr.conv ? launch_mfma_small_conv(mp, kA, kB, mp.Cw % 4 == 0 ? 4 : 2, nsplit, g, as_stream(stream))
+        const int gmax = static_cast<int>(ceil_div(nse / 4, nsplit));  // most groups of four steps a wave has
+        ok = pr.conv ? launch_mfma_small_conv(mp, kA, kB, mp.Cw % 4 == 0 ? 4 : 2, nsplit, gmax, g, as_stream(stream))
                      : launch_mfma_small_matrix(mp, kA, kB, nsplit, g, as_stream(stream));
         if (!ok) return false;
         rc = check_launch(pr.who);

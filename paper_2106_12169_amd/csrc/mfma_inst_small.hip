@@ -6,26 +6,34 @@
 
 namespace apnn {
 
-template <int KA, int KB> static void go(const MfmaParams &p, int vw, int nsplit, unsigned grid, hipStream_t st)
+template <int KA, int KB, int VW> static void go_vw(const MfmaParams &p, int nsplit, int gmax, unsigned grid, hipStream_t st)
 {
-    if (vw == 4 && nsplit == 1) hipLaunchKernelGGL((mfma_small_kernel<KA, KB, 4, true, 1>), dim3(grid), dim3(256), 0, st, p);
-    else if (vw == 4) hipLaunchKernelGGL((mfma_small_kernel<KA, KB, 4, true, 4>), dim3(grid), dim3(256), 0, st, p);
-    else if (nsplit == 1) hipLaunchKernelGGL((mfma_small_kernel<KA, KB, 2, true, 1>), dim3(grid), dim3(256), 0, st, p);
-    else hipLaunchKernelGGL((mfma_small_kernel<KA, KB, 2, true, 4>), dim3(grid), dim3(256), 0, st, p);
+    if (nsplit == 1) hipLaunchKernelGGL((mfma_small_kernel<KA, KB, VW, true, 1>), dim3(grid), dim3(256), 0, st, p);
+    else if (gmax == 1) hipLaunchKernelGGL((mfma_small_kernel<KA, KB, VW, true, 4, 1>), dim3(grid), dim3(256), 0, st, p);
+    else if (gmax == 2) hipLaunchKernelGGL((mfma_small_kernel<KA, KB, VW, true, 4, 2>), dim3(grid), dim3(256), 0, st, p);
+    else hipLaunchKernelGGL((mfma_small_kernel<KA, KB, VW, true, 4>), dim3(grid), dim3(256), 0, st, p);
 }
 
-bool launch_mfma_small_conv(const MfmaParams &p, int kindA, int kindB, int vw, int nsplit, unsigned grid, hipStream_t st)
+// gmax: most groups of four steps a wave of a K-split block has (1, 2, or more)
+template <int KA, int KB> static void go(const MfmaParams &p, int vw, int nsplit, int gmax, unsigned grid, hipStream_t st)
+{
+    if (vw == 4) go_vw<KA, KB, 4>(p, nsplit, gmax, grid, st);
+    else go_vw<KA, KB, 2>(p, nsplit, gmax, grid, st);
+}
+
+bool launch_mfma_small_conv(const MfmaParams &p, int kindA, int kindB, int vw, int nsplit, int gmax, unsigned grid,
+                            hipStream_t st)
 {
     switch (kindA * 3 + kindB) {          // features: 0/1 planes, or -1/+1 with the loader's validity word
-        case 9: go<3, 0>(p, vw, nsplit, grid, st); return true;
-        case 10: go<3, 1>(p, vw, nsplit, grid, st); return true;
-        case 11: go<3, 2>(p, vw, nsplit, grid, st); return true;
-        case 0: go<0, 0>(p, vw, nsplit, grid, st); return true;
-        case 1: go<0, 1>(p, vw, nsplit, grid, st); return true;
-        case 2: go<0, 2>(p, vw, nsplit, grid, st); return true;
-        case 3: go<1, 0>(p, vw, nsplit, grid, st); return true;
-        case 4: go<1, 1>(p, vw, nsplit, grid, st); return true;
-        case 5: go<1, 2>(p, vw, nsplit, grid, st); return true;
+        case 9: go<3, 0>(p, vw, nsplit, gmax, grid, st); return true;
+        case 10: go<3, 1>(p, vw, nsplit, gmax, grid, st); return true;
+        case 11: go<3, 2>(p, vw, nsplit, gmax, grid, st); return true;
+        case 0: go<0, 0>(p, vw, nsplit, gmax, grid, st); return true;
+        case 1: go<0, 1>(p, vw, nsplit, gmax, grid, st); return true;
+        case 2: go<0, 2>(p, vw, nsplit, gmax, grid, st); return true;
+        case 3: go<1, 0>(p, vw, nsplit, gmax, grid, st); return true;
+        case 4: go<1, 1>(p, vw, nsplit, gmax, grid, st); return true;
+        case 5: go<1, 2>(p, vw, nsplit, gmax, grid, st); return true;
         default: return false;
     }
 }

@@ -17,7 +17,8 @@ bool launch_mfma32(const MfmaParams &p, int kindA, int kindB, bool conv, unsigne
 // Small-layer kernel (lane-private operand loads, 32 x 32 tiles); nsplit = 1: one
 // tile per wave (grid = ceil(tiles / 4)), nsplit = 4: one tile per block, K split
 // over its waves (grid = tiles).  vw: conv loader vector width in words (4 or 2).
-bool launch_mfma_small_conv(const MfmaParams &p, int kindA, int kindB, int vw, int nsplit, unsigned grid, hipStream_t st);
+bool launch_mfma_small_conv(const MfmaParams &p, int kindA, int kindB, int vw, int nsplit, int gmax, unsigned grid,
+                            hipStream_t st);
 bool launch_mfma_small_matrix(const MfmaParams &p, int kindA, int kindB, int nsplit, unsigned grid, hipStream_t st);
 
 // K words per chunk of each tile size (must match the instances).

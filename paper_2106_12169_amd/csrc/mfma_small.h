@@ -25,10 +25,12 @@
 
 namespace apnn {
 
-template <int KA, int KB, int VW, bool CONV, int NSPLIT>
+template <int KA, int KB, int VW, bool CONV, int NSPLIT, int GMAX = 5>
 __global__ __launch_bounds__(256) void mfma_small_kernel(const MfmaParams p)
 {
-    constexpr int GMAX = 5;                             // groups of four steps whose loads are in flight together
+    // GMAX: groups of four steps whose loads are in flight together.  The load buffers set the register count and
+    // with it the number of blocks a compute unit holds at once: 2 for layers with a short K and many blocks
+    // (six waves per SIMD), 5 for a long K.
     constexpr int LA = DigitPlanes<KA>::value, LB = DigitPlanes<KB>::value;
     constexpr int RPW = 16 / NSPLIT;                    // accumulator registers a wave finishes in the epilogue
 
