@@ -188,6 +188,32 @@ typedef struct {
 int apnn_layer(const apnn_layer_desc *desc, const uint32_t *W_dev, const uint32_t *X_dev,
                uint32_t *out_packed_dev, void *stream);
 
+/* ---- input layer (Sec. 5.1): 8-bit image with few channels ----------------- */
+
+/* The image's bytes go to the 8-bit integer matrix instruction as they are: one
+ * pass where the 1-bit emulation needs 8 (Sec. 6 makes the same observation for
+ * 8-bit operands on large shapes), no bit decomposition of the image, same
+ * integer results.
+ *
+ * apnn_pack_input_weights: src_dev holds Cout x Cin x R x S values, one per byte
+ * (-1/+1 as int8, or unsigned codes below 2^bits, bits <= 7; S <= 8).  dst_dev
+ * receives apnn_input_weight_bytes(Cout, Cin, R) bytes: signed-byte rows in the
+ * kernel's K order, then one int32 per output channel (128 x the row sum, the
+ * constant that lets the image enter as signed bytes x - 128). */
+size_t apnn_input_weight_bytes(int64_t Cout, int64_t Cin, int R);
+int apnn_pack_input_weights(const void *src_dev, int64_t Cout, int64_t Cin, int R, int S, int bits,
+                            apnn_encoding enc, void *dst_dev, void *stream);
+
+/* Y[n][ho][wo][co] as in apnn_conv2d for image_dev = N x Cin x H x W unsigned
+ * bytes (any Cin >= 1; conv.q is the number of significant bits, conv.encX must
+ * be APNN_ENC_UNSIGNED), W_dev from apnn_pack_input_weights, then the epilogue and
+ * the outputs of apnn_layer (acc_out_dev, float_out_dev, residual, q_out planes in
+ * [pixel][q_out][Cout/32]).  desc->is_gemm and desc->pool must be 0.
+ * APNN_ERR_UNSUPPORTED unless S <= 8, W >= 8, p <= 7, Cout <= 128 and
+ * 255 K max|w| < 2^24. */
+int apnn_input_layer(const apnn_layer_desc *desc, const void *W_dev, const uint8_t *image_dev,
+                     uint32_t *out_packed_dev, void *stream);
+
 /* Fold batch norm (Eq. 5), zero point and step into a', b' on the host
  * (double arithmetic, one rounding to fp32):
  *   a' = gamma / (sqrt(var + eps) * step),  b' = (beta - mean*gamma/sqrt(var+eps) - zero) / step.

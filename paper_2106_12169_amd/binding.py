@@ -27,6 +27,7 @@ EXPORTS = (
     "apnn_last_error", "apnn_row_words", "apnn_packed_words", "apnn_fmap_words",
     "apnn_pack", "apnn_pack_fmap", "apnn_pack_conv_weights", "apnn_pack_patches",
     "apnn_pack_patch_weights", "apnn_quantize", "apnn_gemm", "apnn_conv2d", "apnn_layer",
+    "apnn_input_weight_bytes", "apnn_pack_input_weights", "apnn_input_layer",
     "apnn_fold_bn", "apnn_maxpool", "apnn_sumpool", "apnn_probe_valu", "apnn_probe_copy",
 )
 
@@ -78,13 +79,18 @@ def lib():
     L.apnn_gemm.argtypes = [vp, vp, vp, i64, i64, i64, i32, i32, i32, i32, vp]
     L.apnn_conv2d.argtypes = [C.POINTER(ConvDesc), vp, vp, vp, vp]
     L.apnn_layer.argtypes = [C.POINTER(LayerDesc), vp, vp, vp, vp]
+    L.apnn_input_weight_bytes.restype = C.c_size_t
+    L.apnn_input_weight_bytes.argtypes = [i64, i64, i32]
+    L.apnn_pack_input_weights.argtypes = [vp, i64, i64, i32, i32, i32, i32, vp, vp]
+    L.apnn_input_layer.argtypes = [C.POINTER(LayerDesc), vp, vp, vp, vp]
     L.apnn_fold_bn.argtypes = [vp, vp, vp, vp, C.c_double, C.c_double, C.c_double, i64, vp, vp]
     L.apnn_maxpool.argtypes = [vp, i64, i64, i64, i64, i32, i32, i32, i32, vp, vp]
     L.apnn_sumpool.argtypes = [vp, i64, i64, i64, i64, i32, i32, vp, vp]
     L.apnn_probe_valu.argtypes = [i32, i32, vp, C.POINTER(C.c_double), vp]
     L.apnn_probe_copy.argtypes = [vp, vp, C.c_size_t, vp]
     for name in EXPORTS:
-        if name not in ("apnn_last_error", "apnn_row_words", "apnn_packed_words", "apnn_fmap_words"):
+        if name not in ("apnn_last_error", "apnn_row_words", "apnn_packed_words", "apnn_fmap_words",
+                        "apnn_input_weight_bytes"):
             getattr(L, name).restype = i32
     _lib = L
     return L
@@ -234,6 +240,29 @@ def apnn_layer(d: Conv, W: torch.Tensor, X: torch.Tensor, *, is_gemm: bool = Fal
     L = LayerDesc(d.c(), int(is_gemm), q_out, _ptr(scale), _ptr(bias), _ptr(residual), q_res, res_scale,
                   _ptr(acc_out), _ptr(float_out), pool)
     _check(lib().apnn_layer(C.byref(L), _ptr(W), _ptr(X), _ptr(out) if q_out > 0 else None, _stream()))
+    return out if q_out > 0 else None
+
+
+def apnn_pack_input_weights(src: torch.Tensor, bits: int, enc: int) -> torch.Tensor:
+    """src: Cout x Cin x R x S values, one per byte -> the input layer's signed-byte weight rows."""
+    Cout, Cin, R, S = src.shape
+    out = torch.empty(max(lib().apnn_input_weight_bytes(Cout, Cin, R), 16), dtype=torch.uint8, device=src.device)
+    _check(lib().apnn_pack_input_weights(_ptr(src), Cout, Cin, R, S, bits, enc, _ptr(out), _stream()))
+    return out
+
+
+def apnn_input_layer(d: Conv, W: torch.Tensor, image: torch.Tensor, *, q_out: int = 0,
+                     scale: Optional[torch.Tensor] = None, bias: Optional[torch.Tensor] = None,
+                     residual: Optional[torch.Tensor] = None, q_res: int = 0, res_scale: float = 0.0,
+                     acc_out: Optional[torch.Tensor] = None, float_out: Optional[torch.Tensor] = None,
+                     out: Optional[torch.Tensor] = None) -> Optional[torch.Tensor]:
+    """Convolution of the N x Cin x H x W uint8 image with weights from apnn_pack_input_weights, fused epilogue
+    as in apnn_layer.  Returns the packed output codes (or None when q_out == 0)."""
+    if q_out > 0 and out is None:
+        out = _words(apnn_fmap_words(d.N * d.Ho * d.Wo, d.Cout, q_out), image.device)
+    L = LayerDesc(d.c(), 0, q_out, _ptr(scale), _ptr(bias), _ptr(residual), q_res, res_scale,
+                  _ptr(acc_out), _ptr(float_out), 0)
+    _check(lib().apnn_input_layer(C.byref(L), _ptr(W), _ptr(image), _ptr(out) if q_out > 0 else None, _stream()))
     return out if q_out > 0 else None
 
 

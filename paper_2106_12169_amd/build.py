@@ -23,7 +23,7 @@ LIB = os.path.join(HERE, "libapnn.so")
 SOURCES = ["mfma_inst_256_pm1.hip", "mfma_inst_256_u2.hip", "mfma_inst_256_u1.hip",
            "mfma_inst_128_pm1.hip", "mfma_inst_128_u2.hip", "mfma_inst_128_u1.hip", "mfma_inst_128.hip",
            "mfma_inst_64.hip", "mfma_inst_small.hip", "mfma_inst_small_matrix.hip", "mfma_inst_32.hip",
-           "tile_inst_8.hip", "tile_inst_4.hip", "tile_inst_2.hip", "layer.hip", "pack.hip", "pool.hip",
+           "tile_inst_8.hip", "tile_inst_4.hip", "tile_inst_2.hip", "layer.hip", "input_layer.hip", "pack.hip", "pool.hip",
            "mfma_inst_256.hip", "common.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -3,7 +3,7 @@ Sec. 5.1): marshalling only.
 
 Weights are packed once at construction (off the timed path, as in Sec. 5.1);
 ``forward`` enqueues one library call per node on the current stream: the 8-bit
-image goes through the receptive-field packer, every convolution reads packed
+image goes to the input layer as it is, every other convolution reads packed
 bit planes and writes packed bit planes through the fused epilogue, the last
 layer produces int32 logits without requantisation.  All buffers are
 preallocated so that ``forward`` can be captured in a HIP graph.
@@ -31,7 +31,7 @@ class PackedNet:
                 wv, sc, bi = params[L.name]
                 wd = torch.from_numpy(np.ascontiguousarray(wv)).to(device)
                 if L is first:
-                    self.w[L.name] = B.apnn_pack_patch_weights(wd, L.p, B.ENC_PM1)
+                    self.w[L.name] = B.apnn_pack_input_weights(wd, L.p, B.ENC_PM1)
                 elif L.kind == "fc":
                     self.w[L.name] = B.apnn_pack(wd.reshape(L.Cout, -1), L.p, B.ENC_PM1)
                 else:
@@ -45,8 +45,6 @@ class PackedNet:
                 self.buf[L.name] = torch.empty(B.apnn_packed_words(batch, L.Cout, L.q_out), dtype=torch.int32, device=device)
             else:
                 self.buf[L.name] = torch.empty(B.apnn_fmap_words(pixels, L.Cout, L.q_out), dtype=torch.int32, device=device)
-        self.patches = torch.empty(B.apnn_packed_words(batch * first.Ho * first.Wo, 32 * first.R, first.q),
-                                   dtype=torch.int32, device=device)
         torch.cuda.synchronize()
 
     def forward(self, image: torch.Tensor) -> torch.Tensor:
@@ -55,10 +53,9 @@ class PackedNet:
         for L in self.layers:
             out = self.buf[L.name]
             if L is first:
-                B.apnn_pack_patches(image, L.R, L.S, L.stride, L.pad, L.q, out=self.patches)
-                d = B.Conv(self.batch * L.Ho * L.Wo, 1, 1, 32 * L.R, L.Cout, 1, 1, 1, 0, L.p, L.q)
-                B.apnn_layer(d, self.w[L.name], self.patches, is_gemm=True, q_out=L.q_out,
-                             scale=self.scale[L.name], bias=self.bias[L.name], out=out)
+                d = B.Conv(self.batch, L.H, L.W, L.Cin, L.Cout, L.R, L.S, L.stride, L.pad, L.p, L.q)
+                B.apnn_input_layer(d, self.w[L.name], image, q_out=L.q_out,
+                                   scale=self.scale[L.name], bias=self.bias[L.name], out=out)
             elif L.kind == "conv":
                 d = B.Conv(self.batch, L.H, L.W, L.Cin, L.Cout, L.R, L.S, L.stride, L.pad, L.p, L.q)
                 B.apnn_layer(d, self.w[L.name], self.buf[L.src], q_out=L.q_out,
