@@ -33,21 +33,6 @@ struct InputParams {
     float invR;
 };
 
-// Lane writes of the two halves of a ballot: a[lane LA] = lo, b[lane LB] = hi, other lanes unchanged (a and b
-// may be one register).  The values come from a vector compare just before; the two wait states this chip
-// needs between a vector instruction that writes a scalar register and a vector instruction that reads it are
-// spelled out here, because the compiler does not look into the statement.
-template <int LA, int LB> __device__ __forceinline__ void write_lanes(int &a, int &b, unsigned long long ballot)
-{
-    const int lo = static_cast<int>(ballot), hi = static_cast<int>(ballot >> 32);
-    if (&a == &b)
-        asm("s_nop 1\n\tv_writelane_b32 %0, %1, %3\n\tv_writelane_b32 %0, %2, %4" : "+v"(a) : "s"(lo), "s"(hi), "n"(LA), "n"(LB));
-    else
-        asm("s_nop 1\n\tv_writelane_b32 %0, %2, %4\n\tv_writelane_b32 %1, %3, %5"
-            : "+v"(a), "+v"(b)
-            : "s"(lo), "s"(hi), "n"(LA), "n"(LB));
-}
-
 // One wave per 32-pixel row tile, all NT column tiles of 32 channels; steps of 32 K bytes:
 // lane (half lh, row lr) supplies K bytes 16 lh .. 16 lh + 15 of a step, two segments.
 template <int NT> __global__ __launch_bounds__(256, NT <= 2 ? 4 : 2) void input_conv_kernel(const MfmaParams p, const InputParams q)
@@ -201,7 +186,12 @@ template <int NT> __global__ __launch_bounds__(256, NT <= 2 ? 4 : 2) void input_
                 constexpr int r = decltype(rc)::value;
                 constexpr int s_lo = (8 * (r >> 2) + (r & 3)) * NT + j, s_hi = s_lo + 4 * NT;
                 const unsigned long long bal = __ballot(code[j][r] & (1u << b));
-                write_lanes<(s_lo & 63), (s_hi & 63)>(words[s_lo >> 6], words[s_hi >> 6], bal);
+                if constexpr ((s_lo >> 6) == (s_hi >> 6)) {
+                    write_lanes<(s_lo & 63), (s_hi & 63)>(words[s_lo >> 6], bal);
+                } else {                                // (three column tiles: a row pair can straddle two registers)
+                    write_lanes<(s_lo & 63), (s_lo & 63)>(words[s_lo >> 6], (bal & 0xFFFFFFFFull) | (bal << 32));
+                    write_lanes<(s_hi & 63), (s_hi & 63)>(words[s_hi >> 6], (bal >> 32) | (bal & 0xFFFFFFFF00000000ull));
+                }
             });
         });
 #pragma unroll

@@ -435,9 +435,11 @@ __global__ __launch_bounds__(64 * NWM * NWN, FM * FN >= 16 ? 1 : 2) void mfma_bi
         const int gn = n0 + wn * FN * 32 + j * 32 + lr;
         float sc = 0.0f, bi = 0.0f;
         if (p.scale && gn < p.N) { sc = p.scale[gn]; bi = p.bias[gn]; }
-        static_for<FM * 16>([&](auto irc) {
-            constexpr int i = decltype(irc)::value / 16, r = decltype(irc)::value % 16;
-            finish_value(pe, acc[i][j][r], m0 + wm * FM * 32 + i * 32 + 8 * (r >> 2) + 4 * lh + (r & 3), gn, sc, bi, false, 0u, lr, lh);
+        static_for<FM * 4>([&](auto ikc) {
+            constexpr int i = decltype(ikc)::value / 4, k = decltype(ikc)::value % 4;
+            const int row0 = m0 + wm * FM * 32 + i * 32 + 8 * k;
+            const float v4[4] = {acc[i][j][4 * k], acc[i][j][4 * k + 1], acc[i][j][4 * k + 2], acc[i][j][4 * k + 3]};
+            finish_rows8(pe, v4, row0, gn, sc, bi, load_res_rows8(pe, row0, gn >> 5, lane), lane, lr, lh);
         });
     });
 }

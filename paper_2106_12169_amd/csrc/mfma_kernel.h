@@ -179,6 +179,97 @@ __device__ __forceinline__ void finish_value(const MfmaParams &p, float v, int g
     }
 }
 
+// Lane writes of the two halves of a ballot: reg[lane LA] = low half, reg[lane LB] = high half, other lanes
+// unchanged.  The halves come from a vector compare just before; the two wait states this chip needs between a
+// vector instruction that writes a scalar register and a vector instruction that reads it are spelled out,
+// because the compiler does not look into the statement.
+template <int LA, int LB> __device__ __forceinline__ void write_lanes(int &reg, unsigned long long ballot)
+{
+    const int lo = static_cast<int>(ballot), hi = static_cast<int>(ballot >> 32);
+    asm("s_nop 1\n\tv_writelane_b32 %0, %1, %3\n\tv_writelane_b32 %0, %2, %4" : "+v"(reg) : "s"(lo), "s"(hi), "n"(LA), "n"(LB));
+}
+
+// Residual words of the eight output rows row0 .. row0 + 7 of word column wcol: lane l of the wave returns the
+// word of row row0 + (l & 7), plane l >> 3 (zero where there is none).  One load per wave.
+__device__ __forceinline__ uint32_t load_res_rows8(const MfmaParams &p, int row0, int wcol, int lane)
+{
+    const int b = lane >> 3, row = row0 + (lane & 7);
+    uint32_t w = 0;
+    if (p.res && b < p.q_res && row < p.M && wcol < p.NW)
+        w = p.res[(static_cast<int64_t>(row) * p.q_res + b) * p.NW + wcol];
+    return w;
+}
+
+// finish_value for the four accumulator registers 4 k .. 4 k + 3 of a 32 x 32 tile at once: lane (lr, lh) holds
+// v[i] for output row row0 + 4 lh + i and channel gn (row0 = tile row base + 8 k; gn = tile column base + lr).
+// Same arithmetic and outputs as finish_value, written for few vector instructions per value, which is what
+// bounds a layer that runs a few waves per SIMD: row validity is needed only where something is stored, the
+// residual words arrive by one load per wave (res_words from load_res_rows8, fetched early) and are handed out
+// by lane permutes, and the 8 x q_out plane words are collected by lane writes into one register (lane
+// 8 b + row) and leave in one store.  Every lane of the wave must call it.
+__device__ __forceinline__ void finish_rows8(const MfmaParams &p, const float (&v)[4], int row0, int gn, float sc, float bi,
+                                             uint32_t res_words, int lane, int lr, int lh)
+{
+    const int rows_left = p.M - row0 - 4 * lh;          // v[i] is a real row iff i < rows_left
+    const bool cok = gn < p.N;
+    const int64_t first = static_cast<int64_t>(row0 + 4 * lh) * p.N + gn;
+    const float c0 = static_cast<float>(p.c0);
+    float y[4];                                         // exact integers below 2^24, as the int32 results are
+#pragma unroll
+    for (int i = 0; i < 4; ++i) y[i] = v[i] * p.out_scale + c0;
+    if (p.Y) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (cok && i < rows_left) p.Y[first + static_cast<int64_t>(i) * p.N] = static_cast<int>(y[i]);
+    }
+    if (!p.scale) return;
+    float t[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) t[i] = __fmaf_rn(sc, y[i], bi);
+    if (p.res) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            uint32_t code = 0;
+            for (int b = 0; b < p.q_res; ++b) {
+                const uint32_t w = static_cast<uint32_t>(
+                    __builtin_amdgcn_ds_bpermute(4 * (8 * b + 4 * lh + i), static_cast<int>(res_words)));
+                code |= ((w >> lr) & 1u) << b;
+            }
+            t[i] = __fmaf_rn(p.res_scale, static_cast<float>(code), t[i]);
+        }
+    }
+    if (p.T) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (cok && i < rows_left) p.T[first + static_cast<int64_t>(i) * p.N] = t[i];
+    }
+    if (!p.out) return;
+    // (N is a multiple of 32 whenever planes are written: a 32-column tile has all its channels or none)
+    const float qmax = static_cast<float>((1 << p.q_out) - 1);
+    uint32_t code[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        float f = floorf(t[i]);
+        f = (f >= 0.0f) ? f : 0.0f;
+        f = (f > qmax) ? qmax : f;
+        code[i] = static_cast<uint32_t>(f);
+    }
+    int word = 0;
+    static_for<8>([&](auto bc) {
+        constexpr int b = decltype(bc)::value;
+        if (b < p.q_out) {
+            static_for<4>([&](auto ic) {
+                constexpr int i = decltype(ic)::value;
+                write_lanes<8 * b + i, 8 * b + i + 4>(word, __ballot(code[i] & (1u << b)));
+            });
+        }
+    });
+    const int b = lane >> 3, row = row0 + (lane & 7);
+    const int wcol = gn >> 5;                           // (a block tile can reach beyond N: whole 32-column tiles then)
+    if (b < p.q_out && row < p.M && wcol < p.NW)
+        p.out[(static_cast<int64_t>(row) * p.q_out + b) * p.NW + wcol] = static_cast<uint32_t>(word);
+}
+
 __device__ __forceinline__ int div_by_reciprocal(int n, float inv)
 {
     return static_cast<int>((static_cast<float>(n) + 0.5f) * inv);
@@ -362,8 +453,9 @@ void mfma_fp4_kernel(const MfmaParams p)
     // and residual codes now, so that their latency hides behind the main loop
     constexpr int RPW = 16 / NSPLIT;
     float pre_sc[FN], pre_bi[FN];
-    uint32_t pre_res[NSPLIT > 1 ? FM * FN * RPW : 1];
+    uint32_t pre_res[NSPLIT > 1 ? FM * FN : 1];       // per 32 x 32 tile: the words of the wave's eight rows (load_res_rows8)
     if constexpr (NSPLIT > 1) {
+        static_assert(RPW == 4, "a K-split wave finishes one group of eight rows per 32 x 32 tile");
 #pragma unroll
         for (int j = 0; j < FN; ++j) {
             const int gn = n0 + j * 32 + lr;
@@ -371,16 +463,7 @@ void mfma_fp4_kernel(const MfmaParams p)
             if (p.scale && gn < p.N) { pre_sc[j] = p.scale[gn]; pre_bi[j] = p.bias[gn]; }
 #pragma unroll
             for (int i = 0; i < FM; ++i)
-#pragma unroll
-                for (int rr = 0; rr < RPW; ++rr) {
-                    const int gm = m0 + i * 32 + 8 * ks + 4 * lh + rr;     // accumulator register 4 ks + rr
-                    uint32_t code = 0;
-                    if (p.res && !p.pool && gm < p.M && gn < p.N) {
-                        const uint32_t *rp = p.res + static_cast<int64_t>(gm) * p.q_res * p.NW + (gn >> 5);
-                        for (int b = 0; b < p.q_res; ++b) code |= ((rp[b * p.NW] >> lr) & 1u) << b;
-                    }
-                    pre_res[(i * FN + j) * RPW + rr] = code;
-                }
+                pre_res[i * FN + j] = p.pool ? 0u : load_res_rows8(p, m0 + i * 32 + 8 * ks, (n0 + j * 32) >> 5, lane);
         }
     }
 
@@ -449,10 +532,6 @@ void mfma_fp4_kernel(const MfmaParams p)
         __syncthreads();
     }
 
-    auto finish = [&](float v, int gm, int gn, float sc, float bi, bool have_res, uint32_t res_code) {
-        finish_value(p, v, gm, gn, sc, bi, have_res, res_code, lr, lh);
-    };
-
     if constexpr (NSPLIT == 1) {
         constexpr int SLAB_STRIDE = BN + 4;                     // words; the pad keeps the two lane halves on different banks
         constexpr bool SLAB_FITS = NWM * 32 * SLAB_STRIDE <= TILE_WORDS;
@@ -498,9 +577,11 @@ void mfma_fp4_kernel(const MfmaParams p)
                     finish_value(pq, v, (m0 + wm * FM * 32 + i * 32 + 8 * k + 4 * lh) >> 2, gn, sc, bi, false, 0u, lr, lh);
                 });
             } else {
-                static_for<FM * 16>([&](auto irc) {
-                    constexpr int i = decltype(irc)::value / 16, r = decltype(irc)::value % 16;
-                    finish(acc[i][j][r], m0 + wm * FM * 32 + i * 32 + 8 * (r >> 2) + 4 * lh + (r & 3), gn, sc, bi, false, 0u);
+                static_for<FM * 4>([&](auto ikc) {
+                    constexpr int i = decltype(ikc)::value / 4, k = decltype(ikc)::value % 4;
+                    const int row0 = m0 + wm * FM * 32 + i * 32 + 8 * k;
+                    const float v4[4] = {acc[i][j][4 * k], acc[i][j][4 * k + 1], acc[i][j][4 * k + 2], acc[i][j][4 * k + 3]};
+                    finish_rows8(p, v4, row0, gn, sc, bi, load_res_rows8(p, row0, gn >> 5, lane), lane, lr, lh);
                 });
             }
         });
@@ -536,14 +617,16 @@ void mfma_fp4_kernel(const MfmaParams p)
                 });
                 return;
             }
-            static_for<FM * RPW>([&](auto irc) {
-                constexpr int i = decltype(irc)::value / RPW, rr = decltype(irc)::value % RPW;
-                const int r = ks * RPW + rr;
-                float v = 0.0f;
+            static_for<FM>([&](auto ic) {
+                constexpr int i = decltype(ic)::value;
+                float v4[4];
 #pragma unroll
-                for (int k = 0; k < NSPLIT; ++k) v += sRed[k][(i * FN + j) * 16 + r][lane];
-                finish(v, m0 + i * 32 + 8 * (r >> 2) + 4 * lh + (r & 3), gn, pre_sc[j], pre_bi[j], true,
-                       pre_res[(i * FN + j) * RPW + rr]);
+                for (int rr = 0; rr < 4; ++rr) {
+                    v4[rr] = 0.0f;
+#pragma unroll
+                    for (int k = 0; k < NSPLIT; ++k) v4[rr] += sRed[k][(i * FN + j) * 16 + ks * 4 + rr][lane];
+                }
+                finish_rows8(p, v4, m0 + i * 32 + 8 * ks, gn, pre_sc[j], pre_bi[j], pre_res[i * FN + j], lane, lr, lh);
             });
         });
     }

@@ -127,18 +127,12 @@ __global__ __launch_bounds__(256) void mfma_small_kernel(const MfmaParams p)
     const int gn = n0 + lr;
     float sc = 0.0f, bi = 0.0f;
     if (p.scale && live && gn < p.N) { sc = p.scale[gn]; bi = p.bias[gn]; }
-    uint32_t pre_res[RPW];
+    // (one load per wave and group of eight rows: lane l holds the word of row l & 7, plane l >> 3)
+    constexpr int NG = RPW / 4;                         // groups of four registers = eight rows this wave finishes
+    uint32_t pre_res[NG];
 #pragma unroll
-    for (int rr = 0; rr < RPW; ++rr) {
-        const int r = ks * RPW + rr;
-        const int gm = m0 + 8 * (r >> 2) + 4 * lh + (r & 3);
-        uint32_t code = 0;
-        if (p.res && !p.pool && live && gm < p.M && gn < p.N) {
-            const uint32_t *rp = p.res + static_cast<int64_t>(gm) * p.q_res * p.NW + (gn >> 5);
-            for (int b = 0; b < p.q_res; ++b) code |= ((rp[b * p.NW] >> lr) & 1u) << b;
-        }
-        pre_res[rr] = code;
-    }
+    for (int g = 0; g < NG; ++g)
+        pre_res[g] = (live && !p.pool) ? load_res_rows8(p, m0 + 8 * (NSPLIT > 1 ? ks : g), gn >> 5, lane) : 0u;
 
     // Digit pairs (da, db) and the groups of four steps of each are walked as one
     // flat sequence, GMAX entries at a time with all their loads in flight together,
@@ -235,9 +229,10 @@ __global__ __launch_bounds__(256) void mfma_small_kernel(const MfmaParams p)
             });
             return;
         }
-        static_for<16>([&](auto rc) {
-            constexpr int r = decltype(rc)::value;
-            finish_value(p, acc[r], m0 + 8 * (r >> 2) + 4 * lh + (r & 3), gn, sc, bi, true, pre_res[r], lr, lh);
+        static_for<4>([&](auto kc) {
+            constexpr int k = decltype(kc)::value;
+            const float v4[4] = {acc[4 * k], acc[4 * k + 1], acc[4 * k + 2], acc[4 * k + 3]};
+            finish_rows8(p, v4, m0 + 8 * k, gn, sc, bi, pre_res[k], lane, lr, lh);
         });
     } else {
         // add the partial tiles; wave ks finishes accumulator registers RPW ks .. RPW ks + RPW - 1
@@ -256,14 +251,15 @@ __global__ __launch_bounds__(256) void mfma_small_kernel(const MfmaParams p)
             finish_value(pq, pool4(p.pool, v4[0], v4[1], v4[2], v4[3]), (m0 + 8 * ks + 4 * lh) >> 2, gn, sc, bi, false, 0u, lr, lh);
             return;
         }
+        static_assert(RPW == 4, "a K-split wave finishes one group of eight rows");
+        float v4[4];
 #pragma unroll
-        for (int rr = 0; rr < RPW; ++rr) {
-            const int r = ks * RPW + rr;
-            float v = 0.0f;
+        for (int rr = 0; rr < 4; ++rr) {
+            v4[rr] = 0.0f;
 #pragma unroll
-            for (int k = 0; k < NSPLIT; ++k) v += sRed[k][r][lane];
-            finish_value(p, v, m0 + 8 * (r >> 2) + 4 * lh + (r & 3), gn, sc, bi, true, pre_res[rr], lr, lh);
+            for (int k = 0; k < NSPLIT; ++k) v4[rr] += sRed[k][ks * 4 + rr][lane];
         }
+        finish_rows8(p, v4, m0 + 8 * ks, gn, sc, bi, pre_res[0], lane, lr, lh);
     }
 }
 
