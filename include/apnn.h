@@ -188,6 +188,15 @@ typedef struct {
 int apnn_layer(const apnn_layer_desc *desc, const uint32_t *W_dev, const uint32_t *X_dev,
                uint32_t *out_packed_dev, void *stream);
 
+/* Two layers that do not depend on each other (neither reads what the other
+ * writes), e.g. the 3 x 3 convolution and the 1 x 1 shortcut convolution of a
+ * down-sampling residual block (Sec. 5.1): same arguments, checks and results as
+ * two apnn_layer calls.  Small convolution layers of the same operand kinds
+ * share one kernel launch; any other pair is launched one after the other. */
+int apnn_layer_pair(const apnn_layer_desc *descA, const uint32_t *WA_dev, const uint32_t *XA_dev,
+                    uint32_t *outA_packed_dev, const apnn_layer_desc *descB, const uint32_t *WB_dev,
+                    const uint32_t *XB_dev, uint32_t *outB_packed_dev, void *stream);
+
 /* ---- input layer (Sec. 5.1): 8-bit image with few channels ----------------- */
 
 /* The image's bytes go to the 8-bit integer matrix instruction as they are: one

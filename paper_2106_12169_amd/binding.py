@@ -27,7 +27,7 @@ EXPORTS = (
     "apnn_last_error", "apnn_row_words", "apnn_packed_words", "apnn_fmap_words",
     "apnn_pack", "apnn_pack_fmap", "apnn_pack_conv_weights", "apnn_pack_patches",
     "apnn_pack_patch_weights", "apnn_quantize", "apnn_gemm", "apnn_conv2d", "apnn_layer",
-    "apnn_input_weight_bytes", "apnn_pack_input_weights", "apnn_input_layer",
+    "apnn_layer_pair", "apnn_input_weight_bytes", "apnn_pack_input_weights", "apnn_input_layer",
     "apnn_fold_bn", "apnn_maxpool", "apnn_sumpool", "apnn_probe_valu", "apnn_probe_copy",
 )
 
@@ -79,6 +79,7 @@ def lib():
     L.apnn_gemm.argtypes = [vp, vp, vp, i64, i64, i64, i32, i32, i32, i32, vp]
     L.apnn_conv2d.argtypes = [C.POINTER(ConvDesc), vp, vp, vp, vp]
     L.apnn_layer.argtypes = [C.POINTER(LayerDesc), vp, vp, vp, vp]
+    L.apnn_layer_pair.argtypes = [C.POINTER(LayerDesc), vp, vp, vp, C.POINTER(LayerDesc), vp, vp, vp, vp]
     L.apnn_input_weight_bytes.restype = C.c_size_t
     L.apnn_input_weight_bytes.argtypes = [i64, i64, i32]
     L.apnn_pack_input_weights.argtypes = [vp, i64, i64, i32, i32, i32, i32, vp, vp]
@@ -241,6 +242,22 @@ def apnn_layer(d: Conv, W: torch.Tensor, X: torch.Tensor, *, is_gemm: bool = Fal
                   _ptr(acc_out), _ptr(float_out), pool)
     _check(lib().apnn_layer(C.byref(L), _ptr(W), _ptr(X), _ptr(out) if q_out > 0 else None, _stream()))
     return out if q_out > 0 else None
+
+
+def apnn_layer_pair(a: dict, b: dict) -> None:
+    """Two independent layers, one launch where the library can share it.  a, b: the arguments of apnn_layer as
+    dicts with keys d, W, X and optionally q_out, scale, bias, residual, q_res, res_scale, acc_out, float_out, out,
+    pool; packed outputs must be preallocated (out)."""
+    def desc(k):
+        q_out = k.get("q_out", 0)
+        assert q_out == 0 or k.get("out") is not None, "preallocate the packed output"
+        L = LayerDesc(k["d"].c(), 0, q_out, _ptr(k.get("scale")), _ptr(k.get("bias")), _ptr(k.get("residual")),
+                      k.get("q_res", 0), k.get("res_scale", 0.0), _ptr(k.get("acc_out")), _ptr(k.get("float_out")),
+                      k.get("pool", 0))
+        return L, _ptr(k["W"]), _ptr(k["X"]), (_ptr(k["out"]) if q_out > 0 else None)
+    La, Wa, Xa, Oa = desc(a)
+    Lb, Wb, Xb, Ob = desc(b)
+    _check(lib().apnn_layer_pair(C.byref(La), Wa, Xa, Oa, C.byref(Lb), Wb, Xb, Ob, _stream()))
 
 
 def apnn_pack_input_weights(src: torch.Tensor, bits: int, enc: int) -> torch.Tensor:

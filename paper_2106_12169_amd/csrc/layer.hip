@@ -63,8 +63,18 @@ static int pick_mfma_tile(int64_t M, int64_t N, bool conv)
     return 32;                                  // small layers: one wave tile per block, K split over its waves
 }
 
-// Returns true if the launch was issued (status in rc), false if the path does not apply.
-static bool try_mfma(const Problem &pr, MfmaParams &mp, void *stream, int &rc)
+// What the dispatch decided for a layer that takes the small-layer convolution kernel with K split over the
+// waves of a block: filled in instead of launching when a caller wants to put two such layers into one launch.
+struct SmallPlan {
+    bool ok;
+    MfmaParams mp;
+    int kA, kB, vw, gmax;
+    unsigned grid;
+};
+
+// Returns true if the launch was issued (status in rc), false if the path does not apply.  With a plan, nothing is
+// launched: the plan is filled in if the layer takes the small-layer convolution kernel, and left not ok otherwise.
+static bool try_mfma(const Problem &pr, MfmaParams &mp, void *stream, int &rc, SmallPlan *plan)
 {
     const char *e = std::getenv("APNN_MFMA");
     if (e && std::atoi(e) == 0) return false;
@@ -104,12 +114,21 @@ static bool try_mfma(const Problem &pr, MfmaParams &mp, void *stream, int &rc)
         mp.c0 = (kA == OPK_PM1 && kB == OPK_PM1) ? -static_cast<int>(nse * 64 - pr.Ktotal) : 0;
         const unsigned g = static_cast<unsigned>(nsplit == 1 ? ceil_div(tiles, 4) : tiles);
         const int gmax = static_cast<int>(ceil_div(nse / 4, nsplit));  // most groups of four steps a wave has
+        if (plan) {
+            if (pr.conv && nsplit == 4) {
+                plan->ok = true; plan->mp = mp; plan->kA = kA; plan->kB = kB;
+                plan->vw = mp.Cw % 4 == 0 ? 4 : 2; plan->gmax = gmax; plan->grid = g;
+            }
+            rc = APNN_OK;
+            return true;
+        }
         ok = pr.conv ? launch_mfma_small_conv(mp, kA, kB, mp.Cw % 4 == 0 ? 4 : 2, nsplit, gmax, g, as_stream(stream))
                      : launch_mfma_small_matrix(mp, kA, kB, nsplit, g, as_stream(stream));
         if (!ok) return false;
         rc = check_launch(pr.who);
         return true;
     }
+    if (plan) { rc = APNN_OK; return true; }
     switch (t) {
         case 256: ok = launch_mfma256(mp, kA, kB, pr.conv, grid, as_stream(stream)); break;
         case 128: ok = launch_mfma128(mp, kA, kB, pr.conv, grid, as_stream(stream)); break;
@@ -172,7 +191,7 @@ static int run_tile(const Problem &pr, TileParams &p, int vw, void *stream)
 
 // Matrix-core kernel when it applies, AND+popcount kernel otherwise; both read the
 // same operands and write the same outputs.
-static int run_either(const Problem &pr, TileParams &p, int vw, void *stream)
+static int run_either(const Problem &pr, TileParams &p, int vw, void *stream, SmallPlan *plan)
 {
     MfmaParams mp{};
     mp.A = p.A; mp.B = p.B; mp.M = p.M; mp.N = p.N;
@@ -192,7 +211,8 @@ static int run_either(const Problem &pr, TileParams &p, int vw, void *stream)
     mp.res = p.res; mp.q_res = p.q_res; mp.res_scale = p.res_scale;
     mp.out = p.out; mp.q_out = p.q_out; mp.NW = p.NW;
     int rc = APNN_OK;
-    if (try_mfma(pr, mp, stream, rc)) return rc;
+    if (try_mfma(pr, mp, stream, rc, plan)) return rc;
+    if (plan) return APNN_OK;
     return run_tile(pr, p, vw, stream);
 }
 
@@ -215,8 +235,9 @@ static int check_desc(const char *who, const apnn_conv_desc &d, bool is_gemm)
     return check_int32_range(who, d.Cin * d.R * d.S, d.p, d.q);
 }
 
+// With a plan: validation and dispatch only, nothing is launched (see SmallPlan).
 static int layer_impl(const char *who, const apnn_layer_desc &L, const uint32_t *W_dev, const uint32_t *X_dev,
-                      uint32_t *out_packed, void *stream)
+                      uint32_t *out_packed, void *stream, SmallPlan *plan = nullptr)
 {
     const apnn_conv_desc &d = L.conv;
     const bool is_gemm = L.is_gemm != 0;
@@ -279,7 +300,7 @@ static int layer_impl(const char *who, const apnn_layer_desc &L, const uint32_t 
     }
     p.NW = static_cast<int>(N / 32);
     Problem pr{who, !is_gemm, M, N, is_gemm ? d.Cin : d.Cin * d.R * d.S, p.PA, p.PB, d.encX, d.encW};
-    return run_either(pr, p, vw, stream);
+    return run_either(pr, p, vw, stream, plan);
 }
 
 }  // namespace apnn
@@ -310,7 +331,7 @@ extern "C" int apnn_gemm(const uint32_t *W_dev, const uint32_t *X_dev, int32_t *
     t.Y = Y_dev;
     t.NW = static_cast<int>(N / 32);
     Problem pr{"apnn_gemm", false, M, N, K, p, q, encW, encX};
-    return run_either(pr, t, 4, stream);
+    return run_either(pr, t, 4, stream, nullptr);
 }
 
 extern "C" int apnn_conv2d(const apnn_conv_desc *desc, const uint32_t *W_dev, const uint32_t *X_dev, int32_t *Y_dev,
@@ -331,4 +352,24 @@ extern "C" int apnn_layer(const apnn_layer_desc *desc, const uint32_t *W_dev, co
     clear_error();
     if (!desc) return fail(APNN_ERR_INVALID_ARG, "apnn_layer: desc is null");
     return layer_impl("apnn_layer", *desc, W_dev, X_dev, out_packed_dev, stream);
+}
+
+extern "C" int apnn_layer_pair(const apnn_layer_desc *descA, const uint32_t *WA_dev, const uint32_t *XA_dev,
+                               uint32_t *outA_packed_dev, const apnn_layer_desc *descB, const uint32_t *WB_dev,
+                               const uint32_t *XB_dev, uint32_t *outB_packed_dev, void *stream)
+{
+    clear_error();
+    const char *who = "apnn_layer_pair";
+    if (!descA || !descB) return fail(APNN_ERR_INVALID_ARG, "%s: desc is null", who);
+    SmallPlan a{}, b{};
+    if (int rc = layer_impl(who, *descA, WA_dev, XA_dev, outA_packed_dev, stream, &a)) return rc;
+    if (int rc = layer_impl(who, *descB, WB_dev, XB_dev, outB_packed_dev, stream, &b)) return rc;
+    if (a.ok && b.ok && a.kA == b.kA && a.kB == b.kB && a.vw == b.vw &&
+        static_cast<uint64_t>(a.grid) + b.grid <= 0x7FFFFFFFu) {
+        const int gmax = (a.gmax <= 1 && b.gmax <= 1) ? 1 : 5;
+        if (launch_mfma_small_conv_pair(a.mp, a.grid, b.mp, b.grid, a.kA, a.kB, a.vw, gmax, as_stream(stream)))
+            return check_launch(who);
+    }
+    if (int rc = layer_impl(who, *descA, WA_dev, XA_dev, outA_packed_dev, stream)) return rc;
+    return layer_impl(who, *descB, WB_dev, XB_dev, outB_packed_dev, stream);
 }

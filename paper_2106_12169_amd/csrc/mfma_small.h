@@ -25,8 +25,8 @@
 
 namespace apnn {
 
-template <int KA, int KB, int VW, bool CONV, int NSPLIT, int GMAX = 5>
-__global__ __launch_bounds__(256) void mfma_small_kernel(const MfmaParams p)
+template <int KA, int KB, int VW, bool CONV, int NSPLIT, int GMAX>
+__device__ __forceinline__ void mfma_small_body(const MfmaParams &p, const int block)
 {
     // GMAX: groups of four steps whose loads are in flight together.  The load buffers set the register count and
     // with it the number of blocks a compute unit holds at once: 2 for layers with a short K and many blocks
@@ -43,7 +43,7 @@ __global__ __launch_bounds__(256) void mfma_small_kernel(const MfmaParams p)
 
     // tile of this wave: with NSPLIT = 1 the block covers four consecutive tiles of the row-major tile grid
     const int tilesN = (p.N + 31) / 32, tilesM = (p.M + 31) / 32;
-    const int tile = NSPLIT > 1 ? blockIdx.x : blockIdx.x * 4 + wave;
+    const int tile = NSPLIT > 1 ? block : block * 4 + wave;
     const bool live = tile < tilesM * tilesN;           // trailing waves of the last block have no tile
     const int m0 = (tile / tilesN) * 32, n0 = (tile % tilesN) * 32;
 
@@ -261,6 +261,28 @@ __global__ __launch_bounds__(256) void mfma_small_kernel(const MfmaParams p)
         }
         finish_rows8(p, v4, m0 + 8 * ks, gn, sc, bi, pre_res[0], lane, lr, lh);
     }
+}
+
+template <int KA, int KB, int VW, bool CONV, int NSPLIT, int GMAX = 5>
+__global__ __launch_bounds__(256) void mfma_small_kernel(const MfmaParams p)
+{
+    mfma_small_body<KA, KB, VW, CONV, NSPLIT, GMAX>(p, blockIdx.x);
+}
+
+// Two independent convolution layers in one launch (K split over the four waves of a block): blocks
+// 0 .. blocks0 - 1 work on the first, the others on the second.  A layer this small is mostly launch and
+// drain, so two that do not depend on each other (the 3 x 3 convolution and the 1 x 1 shortcut convolution of a
+// down-sampling residual block, Sec. 5.1) share both.
+struct MfmaPairParams {
+    MfmaParams p[2];
+    int blocks0;
+};
+
+template <int KA, int KB, int VW, int GMAX>
+__global__ __launch_bounds__(256) void mfma_small_pair_kernel(const MfmaPairParams pp)
+{
+    const int second = blockIdx.x >= pp.blocks0 ? 1 : 0;            // block-uniform
+    mfma_small_body<KA, KB, VW, true, 4, GMAX>(pp.p[second], blockIdx.x - (second ? pp.blocks0 : 0));
 }
 
 }  // namespace apnn

@@ -47,20 +47,35 @@ class PackedNet:
                 self.buf[L.name] = torch.empty(B.apnn_fmap_words(pixels, L.Cout, L.q_out), dtype=torch.int32, device=device)
         torch.cuda.synchronize()
 
+    def _conv_args(self, L: NetLayer) -> dict:
+        d = B.Conv(self.batch, L.H, L.W, L.Cin, L.Cout, L.R, L.S, L.stride, L.pad, L.p, L.q)
+        return dict(d=d, W=self.w[L.name], X=self.buf[L.src], q_out=L.q_out, scale=self.scale[L.name],
+                    bias=self.bias[L.name], residual=self.buf[L.res] if L.res else None, q_res=2,
+                    res_scale=L.res_scale, out=self.buf[L.name])
+
     def forward(self, image: torch.Tensor) -> torch.Tensor:
         """image: batch x 3 x H x W uint8 device tensor -> int32 logits batch x classes."""
         first = self.layers[0]
-        for L in self.layers:
+        paired = None
+        for i, L in enumerate(self.layers):
             out = self.buf[L.name]
+            if L is paired:
+                continue
             if L is first:
                 d = B.Conv(self.batch, L.H, L.W, L.Cin, L.Cout, L.R, L.S, L.stride, L.pad, L.p, L.q)
                 B.apnn_input_layer(d, self.w[L.name], image, q_out=L.q_out,
                                    scale=self.scale[L.name], bias=self.bias[L.name], out=out)
             elif L.kind == "conv":
-                d = B.Conv(self.batch, L.H, L.W, L.Cin, L.Cout, L.R, L.S, L.stride, L.pad, L.p, L.q)
-                B.apnn_layer(d, self.w[L.name], self.buf[L.src], q_out=L.q_out,
-                             scale=self.scale[L.name], bias=self.bias[L.name],
-                             residual=self.buf[L.res] if L.res else None, q_res=2, res_scale=L.res_scale, out=out)
+                nxt = self.layers[i + 1] if i + 1 < len(self.layers) else None
+                if (nxt is not None and nxt.kind == "conv" and nxt.src == L.src
+                        and nxt.res != L.name and L.res != nxt.name):
+                    # two convolutions of the same features that do not depend on each other (a down-sampling
+                    # block's 3 x 3 convolution and its 1 x 1 shortcut): one call, one launch
+                    B.apnn_layer_pair(self._conv_args(L), self._conv_args(nxt))
+                    paired = nxt
+                else:
+                    a = self._conv_args(L)
+                    B.apnn_layer(a.pop("d"), a.pop("W"), a.pop("X"), **a)
             elif L.kind == "maxpool":
                 B.apnn_maxpool(self.buf[L.src], self.batch, L.H, L.W, L.Cin, L.q, L.R, L.stride, L.pad, out=out)
             elif L.kind == "sumpool":

@@ -101,6 +101,8 @@ def test_layer_validation():
     assert layer(is_gemm=1)[0] == 1                                         # gemm layer with H = 28
     assert layer(conv=B.Conv(0, 28, 28, 128, 128, 3, 3, 1, 1))[0] == 0      # empty batch
     assert _status(L.apnn_conv2d, None, FAKE, FAKE, FAKE, None)[0] == 1
+    assert _status(L.apnn_layer_pair, None, FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, None)[0] == 1
+    assert _status(L.apnn_input_layer, None, FAKE, FAKE, FAKE, None)[0] == 1
 
 
 def test_fold_bn_matches_oracle_fold():

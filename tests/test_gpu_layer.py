@@ -379,3 +379,73 @@ def test_fused_gemm_layer_all_matrix_tiles(monkeypatch, force, q, q_out, with_re
     codes, pad_bits = hp.unpack_fmap(hp.words_u32(out), BS, 1, 1, Cout, q_out)
     assert np.array_equal(codes.reshape(BS, Cout), want_codes) and pad_bits == 0
     assert len(np.unique(want_codes)) == (1 << q_out)
+
+
+@pytest.mark.parametrize("Cin,Cout,H,with_res_a", [
+    (64, 128, 28, False),      # a stage's first block: 3 x 3 stride 2 and 1 x 1 stride 2 of the same features
+    (128, 256, 14, True),      # longer K for the first, short K for the second (different load depths)
+    (256, 512, 7, False),      # 7 x 7 input, ragged row tiles
+    (32, 64, 12, False),       # one channel word per tap: not the matrix-core kernel, launched one after the other
+])
+def test_layer_pair_equals_oracle(Cin, Cout, H, with_res_a):
+    """apnn_layer_pair (shared launch where the dispatch allows it) against the oracle, layer by layer."""
+    BS = 2
+    Xv = wl.uniform_codes(70 + Cin, (BS, Cin, H, H), 2)
+    Xp = B.apnn_pack_fmap(dev(Xv), B.LAYOUT_NCHW, 2, U)
+    cases = []
+    for idx, (R, stride, pad) in enumerate(((3, 2, 1), (1, 2, 0))):
+        Wv = wl.fair_signs(80 + idx + Cin, (Cout, Cin, R, R))
+        K = Cin * R * R
+        scale = (wl.normals(90 + idx, (Cout,), 1.0, 0.2) / np.sqrt(K * 3.5)).astype(np.float32)
+        bias = wl.normals(95 + idx, (Cout,), 2.0, 0.3)
+        d = B.Conv(BS, H, H, Cin, Cout, R, R, stride, pad, 1, 2, P, U)
+        res = wl.uniform_codes(99, (BS, Cout, d.Ho, d.Wo), 2) if (with_res_a and idx == 0) else None
+        out = torch.empty(B.apnn_fmap_words(BS * d.Ho * d.Wo, Cout, 2), dtype=torch.int32, device="cuda")
+        acc = torch.empty((BS, d.Ho, d.Wo, Cout), dtype=torch.int32, device="cuda")
+        cases.append(dict(Wv=Wv, scale=scale, bias=bias, res=res, d=d, out=out, acc=acc,
+                          args=dict(d=d, W=B.apnn_pack_conv_weights(dev(Wv), 1, P), X=Xp, q_out=2, scale=dev(scale),
+                                    bias=dev(bias), out=out, acc_out=acc,
+                                    residual=B.apnn_pack_fmap(dev(res), B.LAYOUT_NCHW, 2, U) if res is not None else None,
+                                    q_res=2, res_scale=0.5)))
+    B.apnn_layer_pair(cases[0]["args"], cases[1]["args"])
+    torch.cuda.synchronize()
+    for c, (R, stride, pad) in zip(cases, ((3, 2, 1), (1, 2, 0))):
+        d = c["d"]
+        want_acc = oracle.conv2d(c["Wv"], P, 1, Xv, U, 2, stride, pad)
+        want_codes, _ = oracle.epilogue(want_acc, c["scale"], c["bias"], 2, res=c["res"], res_scale=0.5)
+        assert np.array_equal(c["acc"].cpu().numpy().transpose(0, 3, 1, 2), want_acc)
+        codes, pad_bits = hp.unpack_fmap(hp.words_u32(c["out"]), BS, d.Ho, d.Wo, Cout, 2)
+        assert np.array_equal(codes, want_codes) and pad_bits == 0
+
+
+def test_layer_pair_mixed_kinds_and_validation():
+    """A pair whose layers take different kernels (a large matrix layer and a small convolution) still gives both
+    results; an invalid second layer fails before anything is launched."""
+    Xv = wl.uniform_codes(1, (1, 64, 8, 8), 2)
+    Wv = wl.fair_signs(2, (64, 64, 3, 3))
+    d = B.Conv(1, 8, 8, 64, 64, 3, 3, 1, 1, 1, 2, P, U)
+    acc = torch.full((1, 8, 8, 64), -5, dtype=torch.int32, device="cuda")
+    conv = dict(d=d, W=B.apnn_pack_conv_weights(dev(Wv), 1, P), X=B.apnn_pack_fmap(dev(Xv), B.LAYOUT_NCHW, 2, U), acc_out=acc)
+    A = wl.uniform_codes(3, (300, 256), 2)
+    Wm = wl.fair_signs(4, (200, 256))
+    dm = B.Conv(300, 1, 1, 256, 200, 1, 1, 1, 0, 1, 2, P, U)
+    accm = torch.empty((300, 200), dtype=torch.int32, device="cuda")
+    Lm = B.LayerDesc(dm.c(), 1, 0, None, None, None, 0, 0.0, accm.data_ptr(), None, 0)
+    Lc = B.LayerDesc(d.c(), 0, 0, None, None, None, 0, 0.0, acc.data_ptr(), None, 0)
+    Wmp, Amp = B.apnn_pack(dev(Wm), 1, P), B.apnn_pack(dev(A), 2, U)
+    import ctypes as C
+    st = torch.cuda.current_stream().cuda_stream
+    rc = B.lib().apnn_layer_pair(C.byref(Lm), Wmp.data_ptr(), Amp.data_ptr(), None,
+                                 C.byref(Lc), conv["W"].data_ptr(), conv["X"].data_ptr(), None, st)
+    torch.cuda.synchronize()
+    assert rc == 0
+    assert np.array_equal(accm.cpu().numpy(), oracle.gemm(Wm, P, 1, A, U, 2).T)
+    assert np.array_equal(acc.cpu().numpy().transpose(0, 3, 1, 2), oracle.conv2d(Wv, P, 1, Xv, U, 2, 1, 1))
+    # second description invalid (Cin not a multiple of 32): nothing runs, the first output stays as it was
+    acc.fill_(-5)
+    bad = B.Conv(1, 8, 8, 48, 64, 3, 3, 1, 1, 1, 2, P, U)
+    Lb = B.LayerDesc(bad.c(), 0, 0, None, None, None, 0, 0.0, acc.data_ptr(), None, 0)
+    rc = B.lib().apnn_layer_pair(C.byref(Lc), conv["W"].data_ptr(), conv["X"].data_ptr(), None,
+                                 C.byref(Lb), conv["W"].data_ptr(), conv["X"].data_ptr(), None, st)
+    torch.cuda.synchronize()
+    assert rc == 1 and (acc.cpu().numpy() == -5).all()
