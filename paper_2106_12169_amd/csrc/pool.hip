@@ -42,6 +42,50 @@ __global__ __launch_bounds__(256) void maxpool_kernel(const uint32_t *__restrict
         if (t < bits) out[(pix * bits + t) * Cw + cw] = m[t];
 }
 
+// The same for windows up to 3 x 3 and up to BITS planes: all taps are loaded before the first comparison, so the
+// kernel is one memory round trip long instead of one per tap.  A tap outside the frame reads as code 0, which
+// never exceeds the running maximum.
+template <int BITS>
+__global__ __launch_bounds__(256) void maxpool3_kernel(const uint32_t *__restrict__ X, uint32_t *__restrict__ out,
+                                                       int64_t npix_out, int H, int W, int Ho, int Wo, int Cw,
+                                                       int bits, int k, int stride, int pad)
+{
+    const int64_t idx = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (idx >= npix_out * Cw) return;
+    const int64_t pix = idx / Cw;
+    const int cw = static_cast<int>(idx - pix * Cw);
+    const int wo = static_cast<int>(pix % Wo), ho = static_cast<int>((pix / Wo) % Ho);
+    const int64_t n = pix / (static_cast<int64_t>(Wo) * Ho);
+    uint32_t c[9][BITS];
+#pragma unroll
+    for (int r = 0; r < 3; ++r)
+#pragma unroll
+        for (int s = 0; s < 3; ++s) {
+            const int h = ho * stride + r - pad, w = wo * stride + s - pad;
+            const bool ok = r < k && s < k && h >= 0 && h < H && w >= 0 && w < W;
+            const uint32_t *src = X + (((n * H + h) * W + w) * bits) * Cw + cw;
+#pragma unroll
+            for (int t = 0; t < BITS; ++t) c[3 * r + s][t] = (ok && t < bits) ? src[static_cast<int64_t>(t) * Cw] : 0u;
+        }
+    uint32_t m[BITS];
+#pragma unroll
+    for (int t = 0; t < BITS; ++t) m[t] = c[0][t];
+#pragma unroll
+    for (int i = 1; i < 9; ++i) {
+        uint32_t gt = 0u, eq = ~0u;
+#pragma unroll
+        for (int t = BITS - 1; t >= 0; --t) {
+            gt |= eq & c[i][t] & ~m[t];
+            eq &= ~(c[i][t] ^ m[t]);
+        }
+#pragma unroll
+        for (int t = 0; t < BITS; ++t) m[t] = (gt & c[i][t]) | (~gt & m[t]);
+    }
+#pragma unroll
+    for (int t = 0; t < BITS; ++t)
+        if (t < bits) out[(pix * bits + t) * Cw + cw] = m[t];
+}
+
 // Global sum pooling: one block of sixteen waves per (image, group of 64 channels);
 // lane = channel, wave w sums the pixels i = w (mod 16), a handful each, with all
 // their loads in flight together (the kernel is one memory round trip long); wave 0
@@ -135,8 +179,15 @@ extern "C" int apnn_maxpool(const uint32_t *X_dev, int64_t N, int64_t H, int64_t
     const int Cw = static_cast<int>(ceil_div(C, 32));
     const int64_t npix = N * Ho * Wo;
     const unsigned grid = static_cast<unsigned>(ceil_div(npix * Cw, 256));
-    hipLaunchKernelGGL(maxpool_kernel, dim3(grid), dim3(256), 0, as_stream(stream), X_dev, out_dev, npix,
-                       static_cast<int>(H), static_cast<int>(W), Ho, Wo, Cw, bits, k, stride, pad);
+    if (k <= 3 && bits <= 2)
+        hipLaunchKernelGGL(maxpool3_kernel<2>, dim3(grid), dim3(256), 0, as_stream(stream), X_dev, out_dev, npix,
+                           static_cast<int>(H), static_cast<int>(W), Ho, Wo, Cw, bits, k, stride, pad);
+    else if (k <= 3 && bits <= 4)
+        hipLaunchKernelGGL(maxpool3_kernel<4>, dim3(grid), dim3(256), 0, as_stream(stream), X_dev, out_dev, npix,
+                           static_cast<int>(H), static_cast<int>(W), Ho, Wo, Cw, bits, k, stride, pad);
+    else
+        hipLaunchKernelGGL(maxpool_kernel, dim3(grid), dim3(256), 0, as_stream(stream), X_dev, out_dev, npix,
+                           static_cast<int>(H), static_cast<int>(W), Ho, Wo, Cw, bits, k, stride, pad);
     return check_launch("apnn_maxpool");
 }
 

@@ -228,7 +228,8 @@ def test_gemm_layer_fc_shape():
     assert np.array_equal(logits.cpu().numpy(), oracle.gemm(Xv, U, 8, Wv, P, 1))
 
 
-@pytest.mark.parametrize("k,stride,pad,bits,C,H", [(3, 2, 1, 2, 64, 13), (2, 2, 0, 2, 32, 8), (3, 1, 1, 3, 96, 6)])
+@pytest.mark.parametrize("k,stride,pad,bits,C,H", [(3, 2, 1, 2, 64, 13), (2, 2, 0, 2, 32, 8), (3, 1, 1, 3, 96, 6),
+                                                  (5, 2, 2, 2, 32, 11), (3, 2, 1, 8, 32, 9), (1, 1, 0, 1, 64, 5)])
 def test_maxpool(k, stride, pad, bits, C, H):
     Xv = wl.uniform_codes(3, (2, C, H, H), bits)
     Xp = B.apnn_pack_fmap(dev(Xv), B.LAYOUT_NCHW, bits, U)
