@@ -89,6 +89,51 @@ __global__ __launch_bounds__(256) void pack_generic_kernel(const uint8_t *__rest
         if (t < g.bits) dst[dst_index(g, row, t, kw)] = w[t];
 }
 
+// Row-major source (matrix operand or NHWC feature map) whose rows start 16-byte aligned: the same work as
+// pack_generic_kernel with 32-bit index arithmetic and one division; the generic kernel's four 64-bit divisions per
+// thread cost more vector instructions than the bit gathering itself and kept a 16 MiB operand at 2.8 TB/s.
+__global__ __launch_bounds__(256) void pack_rows_kernel(const uint8_t *__restrict__ src, uint32_t *__restrict__ dst,
+                                                        uint32_t total, int K, int ldw, int bits, int pm1)
+{
+    const uint32_t idx = blockIdx.x * 256u + threadIdx.x;
+    if (idx >= total) return;
+    const uint32_t row = idx / static_cast<uint32_t>(ldw);
+    const int kw = static_cast<int>(idx - row * ldw);
+    const uint8_t *s = src + static_cast<size_t>(row) * K;
+    uint32_t w[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    const int k0 = kw * 32;
+    if (k0 + 32 <= K) {
+        const uint4 lo = *reinterpret_cast<const uint4 *>(s + k0);
+        const uint4 hi = *reinterpret_cast<const uint4 *>(s + k0 + 16);
+        const uint32_t d[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            if (pm1) {
+                w[0] |= gather4(positive_bytes(d[i])) << (4 * i);
+            } else {
+#pragma unroll
+                for (int t = 0; t < 8; ++t)
+                    if (t < bits) w[t] |= gather4((d[i] >> t) & 0x01010101u) << (4 * i);
+            }
+        }
+    } else {
+        for (int b = 0; b < 32 && k0 + b < K; ++b) {
+            const uint8_t v = s[k0 + b];
+            if (pm1) {
+                w[0] |= static_cast<uint32_t>(static_cast<int8_t>(v) > 0) << b;
+            } else {
+#pragma unroll
+                for (int t = 0; t < 8; ++t)
+                    if (t < bits) w[t] |= ((static_cast<uint32_t>(v) >> t) & 1u) << b;
+            }
+        }
+    }
+    uint32_t *o = dst + static_cast<size_t>(row) * bits * ldw + kw;
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+        if (t < bits) o[static_cast<size_t>(t) * ldw] = w[t];
+}
+
 __global__ __launch_bounds__(256) void quantize_pack_kernel(const float *__restrict__ src,
                                                             uint32_t *__restrict__ dst, int64_t rows,
                                                             int64_t K, int ldw, int bits, float zero,
@@ -272,8 +317,15 @@ static int launch_pack(const char *who, const void *src, uint32_t *dst, const Pa
     if (total == 0) return APNN_OK;
     if (total > (int64_t(1) << 38)) return fail(APNN_ERR_INVALID_ARG, "%s: tensor too large", who);
     const unsigned grid = static_cast<unsigned>(ceil_div(total, 256));
-    hipLaunchKernelGGL(pack_generic_kernel, dim3(grid), dim3(256), 0, as_stream(stream),
-                       static_cast<const uint8_t *>(src), dst, g);
+    // plain rows of K contiguous bytes, every row 16-byte aligned, destination planes of a row adjacent
+    const bool rows_form = g.k_stride == 1 && g.row_stride == g.K && g.outer_div == g.rows && g.inner_n == 1 &&
+                           g.K % 16 == 0 && aligned16(src) && total < (int64_t(1) << 32) - 256 && g.K <= INT32_MAX;
+    if (rows_form)
+        hipLaunchKernelGGL(pack_rows_kernel, dim3(grid), dim3(256), 0, as_stream(stream), static_cast<const uint8_t *>(src),
+                           dst, static_cast<uint32_t>(total), static_cast<int>(g.K), g.ldw, g.bits, g.pm1);
+    else
+        hipLaunchKernelGGL(pack_generic_kernel, dim3(grid), dim3(256), 0, as_stream(stream),
+                           static_cast<const uint8_t *>(src), dst, g);
     return check_launch(who);
 }
 
