@@ -56,6 +56,21 @@ template <int NT> __global__ __launch_bounds__(256, NT <= 2 ? 4 : 2) void input_
     const int shl = delta > 0 ? 8 * delta : 0, shr = delta < 0 ? -8 * delta : 0;
     const int img_base = n * q.C * p.H * p.W + xs;
 
+    // per-channel parameters of the epilogue: fetched now, their latency hides behind the main loop
+    bool cok[NT];
+    float sc[NT], bi[NT];
+    int ct[NT];
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+        const int gn = 32 * j + lr;
+        cok[j] = gn < p.N;
+        sc[j] = 0.0f; bi[j] = 0.0f; ct[j] = 0;
+        if (cok[j]) {
+            ct[j] = q.cterm[gn];
+            if (p.scale) { sc[j] = p.scale[gn]; bi[j] = p.bias[gn]; }
+        }
+    }
+
     v16i_t acc[NT];
 #pragma unroll
     for (int j = 0; j < NT; ++j)
@@ -109,21 +124,10 @@ template <int NT> __global__ __launch_bounds__(256, NT <= 2 ? 4 : 2) void input_
     const int rows_left = p.M - m0 - 4 * lh;            // accumulator register r is a real row iff row_lo(r) < rows_left
     const int64_t first = static_cast<int64_t>(m0 + 4 * lh);
     auto row_lo = [](int r) { return 8 * (r >> 2) + (r & 3); };     // lane half 0; half 1 has row_lo + 4
-    bool cok[NT];
-    float sc[NT], bi[NT];
 #pragma unroll
-    for (int j = 0; j < NT; ++j) {
-        const int gn = 32 * j + lr;
-        cok[j] = gn < p.N;
-        sc[j] = 0.0f; bi[j] = 0.0f;
-        int ct = 0;
-        if (cok[j]) {
-            ct = q.cterm[gn];
-            if (p.scale) { sc[j] = p.scale[gn]; bi[j] = p.bias[gn]; }
-        }
+    for (int j = 0; j < NT; ++j)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[j][r] += ct;
-    }
+        for (int r = 0; r < 16; ++r) acc[j][r] += ct[j];
     if (p.Y) {
 #pragma unroll
         for (int j = 0; j < NT; ++j) {
