@@ -57,10 +57,12 @@ class PackedNet:
         """image: batch x 3 x H x W uint8 device tensor -> int32 logits batch x classes."""
         first = self.layers[0]
         paired = None
+        self.launches = 0                               # library calls (= kernel launches) of this pass
         for i, L in enumerate(self.layers):
             out = self.buf[L.name]
             if L is paired:
                 continue
+            self.launches += 1
             if L is first:
                 d = B.Conv(self.batch, L.H, L.W, L.Cin, L.Cout, L.R, L.S, L.stride, L.pad, L.p, L.q)
                 B.apnn_input_layer(d, self.w[L.name], image, q_out=L.q_out,
