@@ -163,7 +163,7 @@ def main():
             "kernel_us": round(gemm_s * 1e6, 2),
             # HBM bytes per launch from rocprofv3 FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 (KiB), see
             # profiles/mfma_big_kernel_gemm_w1a2_4096_hbm_counters.txt; algorithmic: 6 MiB in + 64 MiB out
-            "traffic": 10405.4 * 2.0 * 1024 + 65536.0 * 1024,
+            "traffic": 8355.1 * 2.0 * 1024 + 65536.0 * 1024,
             "algorithmic_bytes": (wk.M * wk.p + wk.N * wk.q) * (wk.K // 8) + 4 * wk.M * wk.N,
         },
         "roofline_popcount_kernel": {

@@ -129,6 +129,8 @@ static bool try_mfma(const Problem &pr, MfmaParams &mp, void *stream, int &rc, S
         return true;
     }
     if (plan) { rc = APNN_OK; return true; }
+    if ((t == 256 || t == 128) && !pr.conv)
+        mp.xcd_regions = (ceil_div(pr.M, t) % 2 == 0 && ceil_div(pr.N, t) % 4 == 0) ? 1 : 0;
     switch (t) {
         case 256: ok = launch_mfma256(mp, kA, kB, pr.conv, grid, as_stream(stream)); break;
         case 128: ok = launch_mfma128(mp, kA, kB, pr.conv, grid, as_stream(stream)); break;

@@ -159,7 +159,17 @@ __global__ __launch_bounds__(64 * NWM * NWN, FM * FN >= 16 ? 1 : 2) void mfma_bi
     const int lr = lane & 31, lh = lane >> 5;
 
     const int tilesN = (p.N + BN - 1) / BN;
-    const int m0 = (blockIdx.x / tilesN) * BM, n0 = (blockIdx.x % tilesN) * BN;
+    // Workgroups go to the eight XCDs in turn (block b runs on XCD b mod 8), and every XCD fills its own L2 from
+    // HBM.  When the tile grid divides into 2 x 4 regions, XCD x gets region x instead of every eighth tile of the
+    // row-major order, so the operand rows its L2 pulls are those of a compact rectangle (for 16 x 16 tiles: 8 row
+    // panels + 4 column panels instead of 16 + 2).
+    int tile = blockIdx.x;
+    if (p.xcd_regions) {
+        const int tilesM = (p.M + BM - 1) / BM;
+        const int rw = tilesN >> 2, rh = tilesM >> 1, xcd = tile & 7, idx = tile >> 3;
+        tile = ((xcd >> 2) * rh + idx / rw) * tilesN + (xcd & 3) * rw + idx % rw;
+    }
+    const int m0 = (tile / tilesN) * BM, n0 = (tile % tilesN) * BN;
 
     Fp4Masks2 km;
     km.m2 = reg_const(0x22222222u); km.m3 = reg_const(0x33333333u);

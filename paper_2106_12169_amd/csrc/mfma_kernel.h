@@ -80,6 +80,7 @@ struct MfmaParams {
     // exact for n < 2^21, which the host checks (fastdiv); larger problems divide integers.
     float invS, invWo, invHoWo, invWp, invHpWp;
     int fastdiv;
+    int xcd_regions;         // pipelined large-tile kernel: tile grid walked as 2 x 4 regions, one per XCD (host: grid divides)
     // outputs, as in the AND+popcount kernel
     int32_t *Y;
     float *T;

@@ -157,3 +157,22 @@ def test_large_tile_kernel_full_width_sampled(encW, p, encX, q, K):
     assert np.array_equal(Y[rows], oracle.gemm(W[rows], encW, p, X, encX, q))
     colw = W.astype(np.int64).sum(0)
     assert np.array_equal(Y.astype(np.int64).sum(0), X.astype(np.int64) @ colw)
+
+
+@pytest.mark.parametrize("force,M,N,K", [
+    ("128", 256, 512, 96),         # 2 x 4 tiles: one tile per region
+    ("128", 250, 1000, 333),       # the same grid doubled in N, ragged on every side
+    ("128", 1024, 1536, 160),      # 8 x 12 tiles: regions of 4 x 3
+    ("256", 1024, 2048, 64),       # 4 x 8 tiles of 256
+    ("256", 512, 1000, 200),       # 2 x 4, ragged N
+])
+def test_large_tile_kernel_region_order(monkeypatch, force, M, N, K):
+    """Tile grids that divide into 2 x 4 regions are walked region by region (one per XCD): every tile must still be
+    computed exactly once, whatever the grid."""
+    for v in ("APNN_TILE", "APNN_MFMA", "APNN_MFMA_TILE", "APNN_MFMA_SMALL", "APNN_MFMA_NSPLIT"):
+        monkeypatch.delenv(v, raising=False)
+    monkeypatch.setenv("APNN_MFMA_TILE", force)
+    W = wl.operand(700 + M, M, K, 1, P)
+    X = wl.operand(701 + N, N, K, 2, U)
+    Y = gpu_gemm(W, P, 1, X, U, 2)
+    assert np.array_equal(Y, oracle.gemm(W, P, 1, X, U, 2))
