@@ -114,11 +114,12 @@ template <int NT> __global__ __launch_bounds__(256, NT <= 2 ? 4 : 2) void input_
         }
     }
 
-    // Epilogue: the arithmetic of finish_value, written for few vector instructions per output value.  With
-    // about three waves per SIMD and 2048 output values per wave the kernel's duration is the vector-instruction
-    // count of this part, so row validity and addresses are lane constants made once, and the words of a plane
-    // are collected by lane writes, one per lane, and leave in whole-wave stores: word (row, tile j) of the
-    // 32 x NT words of a plane sits in lane (row NT + j) mod 64 of register (row NT + j) / 64.
+    // Epilogue: the arithmetic of finish_value, written for few vector instructions per output value.  A wave
+    // has 2048 output values and a SIMD about three such waves; the first version spent 50 - 90 instructions
+    // per value and took longer than the rest of the kernel.  Row validity and addresses are lane constants made
+    // once, and the words of a plane are collected by lane writes, one per lane, and leave in whole-wave stores:
+    // word (row, tile j) of the 32 x NT words of a plane sits in lane (row NT + j) mod 64 of register
+    // (row NT + j) / 64.
     // The optional outputs are separate passes over the accumulator registers, each behind one uniform branch.
     constexpr int WR = (32 * NT + 63) / 64;
     const int rows_left = p.M - m0 - 4 * lh;            // accumulator register r is a real row iff row_lo(r) < rows_left
