@@ -265,6 +265,31 @@ def extra_configs(B, wl, dev, graph_time):
     t = graph_time(lambda: net.forward(img), reps=1, replays=50)
     ex["config4_resnet18_w1a2_batch8"] = {"ms": round(t * 1e3, 4), "launches": net.launches,
                                           "what": "HIP-graph replay, 8-bit image in, int32 logits out"}
+
+    # The network's input layer (8-bit image x 1-bit weights, 7 x 7 stride 2) in its three forms: the 8-bit integer
+    # matrix instruction straight from the image, and receptive-field planes multiplied by the FP4 matrix-core
+    # kernel (4 digit passes) or by the AND+popcount kernel (8 plane passes).
+    L = layers[0]
+    wv, sc1, bi1 = wl.network_params(layers)[L.name]
+    sc1, bi1 = dev(sc1), dev(bi1)
+    d1 = B.Conv(8, L.H, L.W, L.Cin, L.Cout, L.R, L.S, L.stride, L.pad, L.p, L.q)
+    out1 = torch.empty(B.apnn_fmap_words(8 * L.Ho * L.Wo, L.Cout, L.q_out), dtype=torch.int32, device="cuda")
+    Wi = B.apnn_pack_input_weights(dev(wv), L.p, B.ENC_PM1)
+    t_i8 = graph_time(lambda: B.apnn_input_layer(d1, Wi, img, q_out=L.q_out, scale=sc1, bias=bi1, out=out1))
+    Wpp = B.apnn_pack_patch_weights(dev(wv), L.p, B.ENC_PM1)
+    patches = torch.empty(B.apnn_packed_words(8 * L.Ho * L.Wo, 32 * L.R, L.q), dtype=torch.int32, device="cuda")
+    dg = B.Conv(8 * L.Ho * L.Wo, 1, 1, 32 * L.R, L.Cout, 1, 1, 1, 0, L.p, L.q)
+
+    def planes_form():
+        B.apnn_pack_patches(img, L.R, L.S, L.stride, L.pad, L.q, out=patches)
+        B.apnn_layer(dg, Wpp, patches, is_gemm=True, q_out=L.q_out, scale=sc1, bias=bi1, out=out1)
+    t_fp4 = graph_time(planes_form)
+    os.environ["APNN_MFMA"] = "0"
+    t_pop = graph_time(planes_form)
+    del os.environ["APNN_MFMA"]
+    ex["config4_input_layer_us"] = {"int8_matrix_instruction_from_image": round(t_i8 * 1e6, 2),
+                                    "patch_planes_fp4_matrix_kernel": round(t_fp4 * 1e6, 2),
+                                    "patch_planes_and_popcount_kernel": round(t_pop * 1e6, 2)}
     return ex
 
 
