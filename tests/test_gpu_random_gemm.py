@@ -1,5 +1,7 @@
 """Seeded random sweep of apnn_gemm over ragged shapes, bit widths, encodings and kernel choices, against the
 oracle (bit-exact)."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -18,7 +20,7 @@ def dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
-@pytest.mark.parametrize("seed", range(50))
+@pytest.mark.parametrize("seed", range(int(os.environ.get("APNN_RANDOM_SEEDS", "50"))))   # more seeds for a longer hunt
 def test_random_gemm(monkeypatch, seed):
     rng = np.random.default_rng(9000 + seed)
     force = FORCES[rng.integers(len(FORCES))]

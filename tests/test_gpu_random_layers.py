@@ -1,6 +1,8 @@
 """Seeded random sweep of apnn_layer over shapes, encodings, bit widths, outputs, residuals, pooling and kernel
 choices, against the oracle: meant to reach the corners the hand-picked cases miss (ragged tiles on every side,
 block tiles that reach beyond M or N, one-plane outputs, eight-plane outputs, residuals of any width)."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -58,7 +60,7 @@ def _draw(rng):
     return c
 
 
-@pytest.mark.parametrize("seed", range(60))
+@pytest.mark.parametrize("seed", range(int(os.environ.get("APNN_RANDOM_SEEDS", "60"))))   # more seeds for a longer hunt
 def test_random_layer(monkeypatch, seed):
     rng = np.random.default_rng(7000 + seed)
     c = _draw(rng)
@@ -106,7 +108,7 @@ def test_random_layer(monkeypatch, seed):
 
 def test_sweep_mostly_computes():
     """The sweep is a parity test only if most draws are computed rather than refused."""
-    if len(OUTCOMES) < 60:
-        pytest.skip("only meaningful after the whole sweep has run in this process")
+    if len(OUTCOMES) < 60 or len(OUTCOMES) > 60:
+        pytest.skip("only meaningful after exactly the default sweep has run in this process")
     refused = sum(1 for _, o in OUTCOMES if o == "refused")
     assert refused <= 15, OUTCOMES
