@@ -123,3 +123,39 @@ def test_input_layer_refusals():
     assert status(lambda: B.apnn_input_layer(B.Conv(1, 16, 16, 3, 64, 3, 3, 1, 1, 1, 8, P, U), Wp, img)) == 1   # no output
     # 7-bit weights with a K beyond the exact range
     assert status(lambda: B.apnn_input_layer(B.Conv(1, 16, 16, 16, 64, 8, 8, 1, 1, 7, 8, U, U), Wp, img, acc_out=acc)) == 2
+
+
+@pytest.mark.parametrize("seed", range(int(__import__("os").environ.get("APNN_RANDOM_SEEDS", "40"))))
+def test_random_input_layer(seed):
+    """Seeded random geometries: the unaligned 8-byte segments, their clamped start and the shifted-in zeros on
+    both sides of the frame, ragged channel tiles and row tiles, every plane count."""
+    rng = np.random.default_rng(5000 + seed)
+    C, R, S = int(rng.integers(1, 5)), int(rng.integers(1, 9)), int(rng.integers(1, 9))
+    stride, pad = int(rng.integers(1, 5)), int(rng.integers(0, 5))
+    H = int(rng.integers(max(1, R - 2 * pad), 30))
+    W = int(rng.integers(max(8, S - 2 * pad), 60))
+    bits = int(rng.integers(1, 9))
+    Cout = int(rng.choice([32, 40, 64, 96, 128, 7]))
+    enc, p = (P, 1) if rng.integers(2) else (U, int(rng.integers(1, 8)))
+    q_out = int(rng.choice([0, 1, 2, 3, 8])) if Cout % 32 == 0 else 0
+    BS = int(rng.integers(1, 4))
+    img = wl.uniform_codes(seed, (BS, C, H, W), bits)
+    Wv = _weights(seed + 1, (Cout, C, R, S), p, enc)
+    d = B.Conv(BS, H, W, C, Cout, R, S, stride, pad, p, bits, enc, U)
+    acc = torch.full((BS, d.Ho, d.Wo, Cout), -7, dtype=torch.int32, device="cuda")
+    K = C * R * S
+    wmax = 1 if enc == P else (1 << p) - 1
+    scale = (wl.normals(seed + 2, (Cout,), 1.0, 0.3) * (1 << max(q_out, 1)) / (np.sqrt(K) * wmax * ((1 << bits) - 1) + 1)).astype(np.float32)
+    bias = wl.normals(seed + 3, (Cout,), 0.4 * (1 << max(q_out, 1)), 0.5)
+    kw = dict(acc_out=acc)
+    if q_out:
+        kw.update(q_out=q_out, scale=dev(scale), bias=dev(bias))
+    out = B.apnn_input_layer(d, B.apnn_pack_input_weights(dev(Wv), p, enc), dev(img), **kw)
+    torch.cuda.synchronize()
+    want = oracle.conv2d(Wv, enc, p, img, U, bits, stride, pad)
+    case = (C, H, W, R, S, stride, pad, bits, Cout, p, enc, q_out)
+    assert np.array_equal(acc.cpu().numpy().transpose(0, 3, 1, 2), want), case
+    if q_out:
+        want_codes, _ = oracle.epilogue(want, scale, bias, q_out)
+        codes, pad_bits = hp.unpack_fmap(hp.words_u32(out), BS, d.Ho, d.Wo, Cout, q_out)
+        assert np.array_equal(codes, want_codes) and pad_bits == 0, case
