@@ -175,10 +175,12 @@ def apnn_pack_patch_weights(src: torch.Tensor, bits: int, enc: int) -> torch.Ten
     return out
 
 
-def apnn_quantize(src: torch.Tensor, zero: float, step: float, bits: int) -> torch.Tensor:
+def apnn_quantize(src: torch.Tensor, zero: float, step: float, bits: int,
+                  out: Optional[torch.Tensor] = None) -> torch.Tensor:
     rows, K = src.shape
     assert src.dtype == torch.float32
-    out = _words(apnn_packed_words(rows, K, bits), src.device)
+    if out is None:
+        out = _words(apnn_packed_words(rows, K, bits), src.device)
     _check(lib().apnn_quantize(_ptr(src), rows, K, zero, step, bits, _ptr(out), _stream()))
     return out
 

@@ -41,6 +41,7 @@
 // wave ballot per plane: the low half of the ballot is the word of row(lh=0), the
 // high half that of row(lh=1).
 #pragma once
+#include "lane_util.h"
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -134,15 +135,6 @@ template <int KIND> __device__ __forceinline__ void expand_fp4(uint32_t x0, uint
     out[4] = out[5] = out[6] = out[7] = 0;
 }
 
-// f(integral_constant<int, 0>), ..., f(integral_constant<int, N-1>)
-template <int N, class F> __device__ __forceinline__ void static_for(F &&f)
-{
-    if constexpr (N > 0) {
-        static_for<N - 1>(f);
-        f(std::integral_constant<int, N - 1>{});
-    }
-}
-
 // Epilogue on one output value: optional int32 store, fused scale/bias, residual,
 // floor/clamp and the ballot-packed planes.  Every lane of the wave must call it
 // (gm differs only between the two lane halves, gn = tile column base + lr).
@@ -178,16 +170,6 @@ __device__ __forceinline__ void finish_value(const MfmaParams &p, float v, int g
             }
         }
     }
-}
-
-// Lane writes of the two halves of a ballot: reg[lane LA] = low half, reg[lane LB] = high half, other lanes
-// unchanged.  The halves come from a vector compare just before; the two wait states this chip needs between a
-// vector instruction that writes a scalar register and a vector instruction that reads it are spelled out,
-// because the compiler does not look into the statement.
-template <int LA, int LB> __device__ __forceinline__ void write_lanes(int &reg, unsigned long long ballot)
-{
-    const int lo = static_cast<int>(ballot), hi = static_cast<int>(ballot >> 32);
-    asm("s_nop 1\n\tv_writelane_b32 %0, %1, %3\n\tv_writelane_b32 %0, %2, %4" : "+v"(reg) : "s"(lo), "s"(hi), "n"(LA), "n"(LB));
 }
 
 // Residual words of the eight output rows row0 .. row0 + 7 of word column wcol: lane l of the wave returns the

@@ -6,6 +6,7 @@
 // them LSB-first into the word of plane t.  The work is HBM-bound: rows*K bytes
 // in, rows*K*bits/8 bytes out.
 #include "common.h"
+#include "lane_util.h"
 
 namespace apnn {
 
@@ -87,6 +88,51 @@ __global__ __launch_bounds__(256) void pack_generic_kernel(const uint8_t *__rest
 #pragma unroll
     for (int t = 0; t < 8; ++t)
         if (t < g.bits) dst[dst_index(g, row, t, kw)] = w[t];
+}
+
+// Quantiser + packer, one wave per 256 consecutive values of a row: lane l converts values l, l + 64, l + 128,
+// l + 192 of the segment (four coalesced 4-byte loads per wave), a ballot over bit t of the i-th code is words
+// 2 i and 2 i + 1 of plane t, and the 8 words x bits planes of the segment are collected by lane writes (lane
+// 8 t + w) and leave in one store.  The arithmetic per value is that of quantize_pack_kernel.
+__global__ __launch_bounds__(256) void quantize_pack_wave_kernel(const float *__restrict__ src, uint32_t *__restrict__ dst,
+                                                                 uint32_t nseg, int segs, int K, int ldw, int bits,
+                                                                 float zero, float step)
+{
+    const int lane = threadIdx.x & 63;
+    const uint32_t wave = blockIdx.x * 4u + (threadIdx.x >> 6);
+    if (wave >= nseg) return;                           // wave-uniform
+    const uint32_t row = wave / static_cast<uint32_t>(segs);
+    const int seg = static_cast<int>(wave - row * segs);
+    const float *s = src + static_cast<size_t>(row) * K;
+    const float hi = static_cast<float>((1 << bits) - 1);
+    uint32_t code[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int k = seg * 256 + 64 * i + lane;
+        uint32_t c = 0;
+        if (k < K) {
+            // (x - z) / s with one rounding per operation, then floor and clamp
+            const float d = __fsub_rn(s[k], zero);
+            const float v = __fdiv_rn(d, step);
+            float f = floorf(v);
+            f = (f >= 0.0f) ? f : 0.0f;          // negatives and NaN -> 0
+            f = (f > hi) ? hi : f;
+            c = static_cast<uint32_t>(f);
+        }
+        code[i] = c;
+    }
+    int word = 0;
+    static_for<8>([&](auto tc) {
+        constexpr int t = decltype(tc)::value;
+        if (t < bits) {
+            static_for<4>([&](auto ic) {
+                constexpr int i = decltype(ic)::value;
+                write_lanes<8 * t + 2 * i, 8 * t + 2 * i + 1>(word, __ballot(code[i] & (1u << t)));
+            });
+        }
+    });
+    const int t = lane >> 3, kw = seg * 8 + (lane & 7);
+    if (t < bits && kw < ldw) dst[(static_cast<size_t>(row) * bits + t) * ldw + kw] = static_cast<uint32_t>(word);
 }
 
 // Row-major source (matrix operand or NHWC feature map) whose rows start 16-byte aligned: the same work as
@@ -451,8 +497,15 @@ extern "C" int apnn_quantize(const float *src_dev, int64_t rows, int64_t K, floa
     if (!src_dev || !dst_dev) return fail(APNN_ERR_INVALID_ARG, "apnn_quantize: null pointer");
     if (!aligned16(dst_dev)) return fail(APNN_ERR_ALIGNMENT, "apnn_quantize: dst_dev not 16-byte aligned");
     const int ldw = static_cast<int>(apnn_row_words(K));
-    const unsigned grid = static_cast<unsigned>(ceil_div(rows * ldw, 256));
-    hipLaunchKernelGGL(quantize_pack_kernel, dim3(grid), dim3(256), 0, as_stream(stream), src_dev, dst_dev, rows, K,
-                       ldw, bits, zero, step);
+    const int64_t segs = ceil_div(K, 256), nseg = rows * segs;
+    if (nseg < (int64_t(1) << 32) - 4 && K <= INT32_MAX) {
+        hipLaunchKernelGGL(quantize_pack_wave_kernel, dim3(static_cast<unsigned>(ceil_div(nseg, 4))), dim3(256), 0,
+                           as_stream(stream), src_dev, dst_dev, static_cast<uint32_t>(nseg), static_cast<int>(segs),
+                           static_cast<int>(K), ldw, bits, zero, step);
+    } else {
+        const unsigned grid = static_cast<unsigned>(ceil_div(rows * ldw, 256));
+        hipLaunchKernelGGL(quantize_pack_kernel, dim3(grid), dim3(256), 0, as_stream(stream), src_dev, dst_dev, rows, K,
+                           ldw, bits, zero, step);
+    }
     return check_launch("apnn_quantize");
 }

@@ -61,11 +61,12 @@ def test_pack_conv_weights_layout():
         assert np.array_equal(plane.reshape(Cout, R, S, Cin), ((w2 >> t) & 1).transpose(0, 2, 3, 1))
 
 
+@pytest.mark.parametrize("rows,K", [(19, 333), (5, 256), (3, 1), (7, 31), (2, 1000), (64, 4096)])
 @pytest.mark.parametrize("bits", [1, 2, 4, 8])
-def test_quantize_matches_oracle(bits):
-    rows, K = 19, 333
+def test_quantize_matches_oracle(bits, rows, K):
     x = wl.normals(9, (rows, K), 2.0, 3.0)
-    x[0, :6] = [np.nan, np.inf, -np.inf, 0.0, -0.0, 1e30]
+    special = [np.nan, np.inf, -np.inf, 0.0, -0.0, 1e30][:K]
+    x[0, :len(special)] = special
     zero, step = -0.75, 0.37
     words = hp.words_u32(B.apnn_quantize(dev(x), zero, step, bits))
     codes, pad = hp.unpack_matrix(words, rows, K, bits)
