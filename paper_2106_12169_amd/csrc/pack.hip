@@ -180,6 +180,48 @@ __global__ __launch_bounds__(256) void pack_rows_kernel(const uint8_t *__restric
         if (t < bits) o[static_cast<size_t>(t) * ldw] = w[t];
 }
 
+// N x C x H x W source into the fmap layout.  A block owns 256 consecutive pixels of one image: wave w takes the
+// channel words w, w + 4, ...; lane = four consecutive pixels, one dword load per channel, contiguous across the
+// wave.  The plane words go to an LDS image of the block's output record ([pixel][plane][channel word], the pixel
+// stride padded to an odd number of words) and leave as contiguous 4-byte-per-lane stores: both sides of the
+// transposition are coalesced.  H W must be a multiple of 4 and the source 4-byte aligned (otherwise the generic
+// kernel, one byte per load, takes over); dynamic LDS: 256 * (bits * Cw | 1) words.
+__global__ __launch_bounds__(256) void pack_nchw_kernel(const uint8_t *__restrict__ src, uint32_t *__restrict__ dst,
+                                                        int C, int HW, int Cw, int bits, int pm1, int blocks_per_image)
+{
+    extern __shared__ uint32_t rec[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n = blockIdx.x / blocks_per_image, p0 = (blockIdx.x - n * blocks_per_image) * 256;   // first pixel of the block
+    const int npix = min(256, HW - p0);                 // a multiple of 4
+    const int RW = bits * Cw, PS = RW | 1;              // words per pixel record, padded stride in LDS
+    const bool have = 4 * lane < npix;
+    for (int cw = wave; cw < Cw; cw += 4) {
+        const uint8_t *s = src + (static_cast<size_t>(n) * C + 32 * cw) * HW + p0 + 4 * lane;
+        uint32_t d[32];
+#pragma unroll
+        for (int c = 0; c < 32; ++c) {
+            d[c] = (have && 32 * cw + c < C) ? *reinterpret_cast<const uint32_t *>(s + static_cast<size_t>(c) * HW) : 0u;
+            if (pm1) d[c] = positive_bytes(d[c]);       // bit 0 of every byte: value > 0
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int t = 0; t < 8; ++t)
+                if (t < bits) {
+                    uint32_t w = 0;
+#pragma unroll
+                    for (int c = 0; c < 32; ++c) w |= ((d[c] >> (8 * j + t)) & 1u) << c;
+                    rec[(4 * lane + j) * PS + t * Cw + cw] = w;
+                }
+    }
+    __syncthreads();
+    uint32_t *o = dst + (static_cast<size_t>(n) * HW + p0) * RW;
+    for (int i = threadIdx.x; i < npix * RW; i += 256) {
+        const int px = i / RW;
+        o[i] = rec[px * PS + (i - px * RW)];
+    }
+}
+
 __global__ __launch_bounds__(256) void quantize_pack_kernel(const float *__restrict__ src,
                                                             uint32_t *__restrict__ dst, int64_t rows,
                                                             int64_t K, int ldw, int bits, float zero,
@@ -412,6 +454,14 @@ extern "C" int apnn_pack_fmap(const void *src_dev, apnn_layout layout, int64_t N
         g.row_stride = C; g.k_stride = 1; g.outer_div = g.rows; g.outer_stride = 0;
     } else {
         g.row_stride = 1; g.k_stride = HW; g.outer_div = HW; g.outer_stride = C * HW;
+        const int64_t bpi = ceil_div(HW, 256), lds = 4 * 256 * ((static_cast<int64_t>(bits) * g.ldw) | 1);
+        if (HW % 4 == 0 && (reinterpret_cast<uintptr_t>(src_dev) & 3u) == 0 && N * bpi <= 0x7FFFFFFF && lds <= 48 * 1024 &&
+            HW <= INT32_MAX - 256 && C <= INT32_MAX - 32) {
+            hipLaunchKernelGGL(pack_nchw_kernel, dim3(static_cast<unsigned>(N * bpi)), dim3(256), static_cast<size_t>(lds),
+                               as_stream(stream), static_cast<const uint8_t *>(src_dev), dst_dev, static_cast<int>(C),
+                               static_cast<int>(HW), g.ldw, bits, g.pm1, static_cast<int>(bpi));
+            return check_launch("apnn_pack_fmap");
+        }
     }
     return launch_pack("apnn_pack_fmap", src_dev, dst_dev, g, stream);
 }

@@ -86,14 +86,14 @@ __global__ __launch_bounds__(256) void maxpool3_kernel(const uint32_t *__restric
         if (t < bits) out[(pix * bits + t) * Cw + cw] = m[t];
 }
 
-// Global sum pooling: one block of sixteen waves per (image, group of 64 channels);
-// lane = channel, wave w sums the pixels i = w (mod 16), a handful each, with all
-// their loads in flight together (the kernel is one memory round trip long); wave 0
-// adds the partial sums and packs the result planes by ballot.
-__global__ __launch_bounds__(1024) void sumpool_kernel(const uint32_t *__restrict__ X, uint32_t *__restrict__ out,
-                                                       int HW, int C, int Cw, int bits, int out_bits, int ldw)
+// Global sum pooling: one block of NWAVE waves per (image, group of 64 channels); lane = channel, wave w sums
+// the pixels i = w (mod NWAVE), a handful each, with all their loads in flight together (the kernel is one
+// memory round trip long); wave 0 adds the partial sums and packs the result planes by ballot.  Sixteen waves
+// for a small batch (few blocks, latency bound), one wave when the batch alone fills the chip.
+template <int NWAVE>
+__global__ __launch_bounds__(64 * NWAVE) void sumpool_kernel(const uint32_t *__restrict__ X, uint32_t *__restrict__ out,
+                                                             int HW, int C, int Cw, int bits, int out_bits, int ldw)
 {
-    constexpr int NWAVE = 16;
     __shared__ uint32_t part[NWAVE][64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n = blockIdx.y, c = blockIdx.x * 64 + lane;
@@ -105,12 +105,14 @@ __global__ __launch_bounds__(1024) void sumpool_kernel(const uint32_t *__restric
         for (int i = wave; i < HW; i += NWAVE)
             for (int t = 0; t < bits; ++t) sum += ((src[(static_cast<int64_t>(i) * bits + t) * Cw] >> cb) & 1u) << t;
     }
-    part[wave][lane] = sum;
-    __syncthreads();
-    if (wave != 0) return;
-    sum = 0;
+    if (NWAVE > 1) {
+        part[wave][lane] = sum;
+        __syncthreads();
+        if (wave != 0) return;
+        sum = 0;
 #pragma unroll
-    for (int w = 0; w < NWAVE; ++w) sum += part[w][lane];
+        for (int w = 0; w < NWAVE; ++w) sum += part[w][lane];
+    }
     for (int b = 0; b < out_bits; ++b) {
         const unsigned long long mask = __ballot((sum >> b) & 1u);
         uint32_t *dst = out + (static_cast<int64_t>(n) * out_bits + b) * ldw + 2 * blockIdx.x;
@@ -205,8 +207,13 @@ extern "C" int apnn_sumpool(const uint32_t *X_dev, int64_t N, int64_t H, int64_t
     if (!X_dev || !out_dev) return fail(APNN_ERR_INVALID_ARG, "apnn_sumpool: null pointer");
     const int ldw = static_cast<int>(apnn_row_words(C));
     const int Cw = static_cast<int>(ceil_div(C, 32));
-    hipLaunchKernelGGL(sumpool_kernel, dim3(ldw / 2, static_cast<unsigned>(N)), dim3(1024), 0, as_stream(stream), X_dev,
-                       out_dev, static_cast<int>(H * W), static_cast<int>(C), Cw, bits, out_bits, ldw);
+    const dim3 grid(ldw / 2, static_cast<unsigned>(N));
+    if (N * (ldw / 2) >= 1024)
+        hipLaunchKernelGGL(sumpool_kernel<1>, grid, dim3(64), 0, as_stream(stream), X_dev, out_dev, static_cast<int>(H * W),
+                           static_cast<int>(C), Cw, bits, out_bits, ldw);
+    else
+        hipLaunchKernelGGL(sumpool_kernel<16>, grid, dim3(1024), 0, as_stream(stream), X_dev, out_dev,
+                           static_cast<int>(H * W), static_cast<int>(C), Cw, bits, out_bits, ldw);
     return check_launch("apnn_sumpool");
 }
 

@@ -239,12 +239,13 @@ def test_maxpool(k, stride, pad, bits, C, H):
     assert np.array_equal(codes, want)
 
 
-@pytest.mark.parametrize("C,H", [(512, 7), (64, 3), (96, 5)])
-def test_sumpool(C, H):
-    Xv = wl.uniform_codes(4, (3, C, H, H), 2)
+@pytest.mark.parametrize("BS,C,H", [(3, 512, 7), (3, 64, 3), (3, 96, 5), (260, 256, 4), (1100, 40, 2)])
+def test_sumpool(BS, C, H):
+    """Small batches take the sixteen-wave blocks, large ones a wave per (image, 64 channels)."""
+    Xv = wl.uniform_codes(4, (BS, C, H, H), 2)
     Xp = B.apnn_pack_fmap(dev(Xv), B.LAYOUT_NCHW, 2, U)
-    out = B.apnn_sumpool(Xp, 3, H, H, C, 2, 8)
-    codes, pad = hp.unpack_matrix(hp.words_u32(out), 3, C, 8)
+    out = B.apnn_sumpool(Xp, BS, H, H, C, 2, 8)
+    codes, pad = hp.unpack_matrix(hp.words_u32(out), BS, C, 8)
     assert np.array_equal(codes, oracle.sumpool(Xv)) and pad == 0
 
 

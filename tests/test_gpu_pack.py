@@ -37,13 +37,24 @@ def test_pack_ignores_bits_above_the_declared_width():
 
 
 @pytest.mark.parametrize("layout", [B.LAYOUT_NHWC, B.LAYOUT_NCHW])
-@pytest.mark.parametrize("N,C,H,W,bits", [(2, 64, 5, 7, 2), (1, 128, 9, 9, 2), (3, 32, 4, 4, 3), (1, 96, 6, 5, 1)])
+@pytest.mark.parametrize("N,C,H,W,bits", [(2, 64, 5, 7, 2), (1, 128, 9, 9, 2), (3, 32, 4, 4, 3), (1, 96, 6, 5, 1),
+                                          (2, 64, 8, 8, 8), (1, 96, 6, 6, 2), (2, 40, 4, 6, 3), (3, 160, 28, 28, 2)])
 def test_pack_fmap(layout, N, C, H, W, bits):
     nchw = wl.uniform_codes(7, (N, C, H, W), bits)
     src = nchw if layout == B.LAYOUT_NCHW else nchw.transpose(0, 2, 3, 1)
     words = hp.words_u32(B.apnn_pack_fmap(dev(src), layout, bits, U))
     codes, pad = hp.unpack_fmap(words, N, H, W, C, bits)
     assert np.array_equal(codes, nchw) and pad == 0
+
+
+@pytest.mark.parametrize("layout", [B.LAYOUT_NHWC, B.LAYOUT_NCHW])
+@pytest.mark.parametrize("N,C,H,W", [(2, 64, 4, 6), (1, 96, 5, 5), (2, 40, 8, 2)])
+def test_pack_fmap_pm1(layout, N, C, H, W):
+    nchw = wl.fair_signs(8, (N, C, H, W))
+    src = nchw if layout == B.LAYOUT_NCHW else nchw.transpose(0, 2, 3, 1)
+    words = hp.words_u32(B.apnn_pack_fmap(dev(src), layout, 1, P))
+    codes, pad = hp.unpack_fmap(words, N, H, W, C, 1)
+    assert np.array_equal(codes, hp.pm1_to_bits(nchw)) and pad == 0
 
 
 def test_pack_conv_weights_layout():
