@@ -239,7 +239,7 @@ def test_maxpool(k, stride, pad, bits, C, H):
     assert np.array_equal(codes, want)
 
 
-@pytest.mark.parametrize("BS,C,H", [(3, 512, 7), (3, 64, 3), (3, 96, 5), (260, 256, 4), (1100, 40, 2)])
+@pytest.mark.parametrize("BS,C,H", [(3, 512, 7), (3, 64, 3), (3, 96, 5), (260, 256, 4), (1100, 40, 2), (2100, 130, 2)])
 def test_sumpool(BS, C, H):
     """Small batches take the sixteen-wave blocks, large ones a wave per (image, 64 channels)."""
     Xv = wl.uniform_codes(4, (BS, C, H, H), 2)
