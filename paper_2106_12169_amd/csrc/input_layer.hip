@@ -168,6 +168,48 @@ template <int NT> __global__ __launch_bounds__(256, NT <= 2 ? 4 : 2) void input_
     }
     if (!p.out) return;
     // (N is a multiple of 32 from here on: every lane has a channel)
+    const int64_t out_row = static_cast<int64_t>(p.q_out) * p.NW;
+    auto store_plane = [&](int b, const int (&words)[WR]) {
+#pragma unroll
+        for (int w = 0; w < WR; ++w) {
+            const int slot = 64 * w + lane, row = slot / NT, j = slot - row * NT;
+            if (row < 32 && m0 + row < p.M) p.out[(m0 + row) * out_row + b * p.NW + j] = static_cast<uint32_t>(words[w]);
+        }
+    };
+    // both rows of a ballot into the plane's word registers
+    auto gather = [&](auto jc, auto rc, int (&words)[WR], unsigned long long bal) {
+        constexpr int j = decltype(jc)::value, r = decltype(rc)::value;
+        constexpr int s_lo = (8 * (r >> 2) + (r & 3)) * NT + j, s_hi = s_lo + 4 * NT;
+        if constexpr ((s_lo >> 6) == (s_hi >> 6)) {
+            write_lanes<(s_lo & 63), (s_hi & 63)>(words[s_lo >> 6], bal);
+        } else {                                        // (three column tiles: a row pair can straddle two registers)
+            write_lanes<(s_lo & 63), (s_lo & 63)>(words[s_lo >> 6], (bal & 0xFFFFFFFFull) | (bal << 32));
+            write_lanes<(s_hi & 63), (s_hi & 63)>(words[s_hi >> 6], (bal >> 32) | (bal & 0xFFFFFFFF00000000ull));
+        }
+    };
+    if (p.q_out <= 2) {
+        // one or two planes straight from compares of t (as in finish_rows8): bit 1 = t >= 2,
+        // bit 0 = (1 <= t < 2) or t >= 3; one plane: bit 0 = t >= 1
+        int w0[WR], w1[WR];
+#pragma unroll
+        for (int w = 0; w < WR; ++w) { w0[w] = 0; w1[w] = 0; }
+        static_for<NT>([&](auto jc) {
+            static_for<16>([&](auto rc) {
+                const float tv = t[decltype(jc)::value][decltype(rc)::value];
+                const unsigned long long c1 = __ballot(tv >= 1.0f);
+                if (p.q_out == 1) {
+                    gather(jc, rc, w0, c1);
+                } else {
+                    const unsigned long long c2 = __ballot(tv >= 2.0f), c3 = __ballot(tv >= 3.0f);
+                    gather(jc, rc, w0, (c1 & ~c2) | c3);
+                    gather(jc, rc, w1, c2);
+                }
+            });
+        });
+        store_plane(0, w0);
+        if (p.q_out == 2) store_plane(1, w1);
+        return;
+    }
     const float qmax = static_cast<float>((1 << p.q_out) - 1);
     uint32_t code[NT][16];
 #pragma unroll
@@ -179,31 +221,17 @@ template <int NT> __global__ __launch_bounds__(256, NT <= 2 ? 4 : 2) void input_
             f = (f > qmax) ? qmax : f;
             code[j][r] = static_cast<uint32_t>(f);
         }
-    const int64_t out_row = static_cast<int64_t>(p.q_out) * p.NW;
 #pragma unroll 1
     for (int b = 0; b < p.q_out; ++b) {
         int words[WR];
 #pragma unroll
         for (int w = 0; w < WR; ++w) words[w] = 0;
         static_for<NT>([&](auto jc) {
-            constexpr int j = decltype(jc)::value;
             static_for<16>([&](auto rc) {
-                constexpr int r = decltype(rc)::value;
-                constexpr int s_lo = (8 * (r >> 2) + (r & 3)) * NT + j, s_hi = s_lo + 4 * NT;
-                const unsigned long long bal = __ballot(code[j][r] & (1u << b));
-                if constexpr ((s_lo >> 6) == (s_hi >> 6)) {
-                    write_lanes<(s_lo & 63), (s_hi & 63)>(words[s_lo >> 6], bal);
-                } else {                                // (three column tiles: a row pair can straddle two registers)
-                    write_lanes<(s_lo & 63), (s_lo & 63)>(words[s_lo >> 6], (bal & 0xFFFFFFFFull) | (bal << 32));
-                    write_lanes<(s_hi & 63), (s_hi & 63)>(words[s_hi >> 6], (bal >> 32) | (bal & 0xFFFFFFFF00000000ull));
-                }
+                gather(jc, rc, words, __ballot(code[decltype(jc)::value][decltype(rc)::value] & (1u << b)));
             });
         });
-#pragma unroll
-        for (int w = 0; w < WR; ++w) {
-            const int slot = 64 * w + lane, row = slot / NT, j = slot - row * NT;
-            if (row < 32 && m0 + row < p.M) p.out[(m0 + row) * out_row + b * p.NW + j] = static_cast<uint32_t>(words[w]);
-        }
+        store_plane(b, words);
     }
 }
 

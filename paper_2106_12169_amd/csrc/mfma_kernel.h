@@ -228,25 +228,43 @@ __device__ __forceinline__ void finish_rows8(const MfmaParams &p, const float (&
     }
     if (!p.out) return;
     // (N is a multiple of 32 whenever planes are written: a 32-column tile has all its channels or none)
-    const float qmax = static_cast<float>((1 << p.q_out) - 1);
-    uint32_t code[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        float f = floorf(t[i]);
-        f = (f >= 0.0f) ? f : 0.0f;
-        f = (f > qmax) ? qmax : f;
-        code[i] = static_cast<uint32_t>(f);
-    }
     int word = 0;
-    static_for<8>([&](auto bc) {
-        constexpr int b = decltype(bc)::value;
-        if (b < p.q_out) {
-            static_for<4>([&](auto ic) {
-                constexpr int i = decltype(ic)::value;
-                write_lanes<8 * b + i, 8 * b + i + 4>(word, __ballot(code[i] & (1u << b)));
-            });
+    if (p.q_out <= 2) {
+        // One or two planes: floor(t) >= k is t >= k for an integer k, so the planes of clamp(floor(t), 0, 3) are
+        // compares of t itself (NaN compares false everywhere: code 0, as the clamp gives): bit 1 = t >= 2,
+        // bit 0 = (1 <= t < 2) or t >= 3; with one plane, bit 0 = t >= 1.  No floor, clamp or conversion: a third
+        // fewer vector instructions, which is what a large layer's duration consists of.
+        static_for<4>([&](auto ic) {
+            constexpr int i = decltype(ic)::value;
+            const unsigned long long c1 = __ballot(t[i] >= 1.0f);
+            if (p.q_out == 1) {
+                write_lanes<i, i + 4>(word, c1);
+            } else {
+                const unsigned long long c2 = __ballot(t[i] >= 2.0f), c3 = __ballot(t[i] >= 3.0f);
+                write_lanes<i, i + 4>(word, (c1 & ~c2) | c3);
+                write_lanes<8 + i, 8 + i + 4>(word, c2);
+            }
+        });
+    } else {
+        const float qmax = static_cast<float>((1 << p.q_out) - 1);
+        uint32_t code[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float f = floorf(t[i]);
+            f = (f >= 0.0f) ? f : 0.0f;
+            f = (f > qmax) ? qmax : f;
+            code[i] = static_cast<uint32_t>(f);
         }
-    });
+        static_for<8>([&](auto bc) {
+            constexpr int b = decltype(bc)::value;
+            if (b < p.q_out) {
+                static_for<4>([&](auto ic) {
+                    constexpr int i = decltype(ic)::value;
+                    write_lanes<8 * b + i, 8 * b + i + 4>(word, __ballot(code[i] & (1u << b)));
+                });
+            }
+        });
+    }
     const int b = lane >> 3, row = row0 + (lane & 7);
     const int wcol = gn >> 5;                           // (a block tile can reach beyond N: whole 32-column tiles then)
     if (b < p.q_out && row < p.M && wcol < p.NW)
