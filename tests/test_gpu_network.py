@@ -62,3 +62,17 @@ def test_resnet18_shape_batch8_logits_and_graph_replay():
         g.replay()
         torch.cuda.synchronize()
         assert np.array_equal(net.buf["fc"].cpu().numpy(), want["fc"])
+
+
+def test_resnet18_shape_batch32_every_node():
+    """A larger batch takes other kernel variants (one tile per wave instead of K split over a block's waves, no
+    paired launches for the early stages): every node against the chained oracle again."""
+    layers = wl.resnet18_layers()
+    params = wl.network_params(layers)
+    img = wl.image_batch(2005, 32, 224)
+    net = PackedNet(layers, params, 32)
+    logits = net.forward(torch.from_numpy(img).cuda())
+    torch.cuda.synchronize()
+    want = onet.run(layers, params, img)
+    _check_all_nodes(layers, net, want, 32)
+    assert np.array_equal(logits.cpu().numpy(), want["fc"])
