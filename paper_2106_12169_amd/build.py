@@ -22,7 +22,7 @@ LIB = os.path.join(HERE, "libapnn.so")
 # slowest translation units first, so that the parallel build is not left waiting for them
 SOURCES = ["mfma_inst_256_pm1.hip", "mfma_inst_256_u2.hip", "mfma_inst_256_u1.hip",
            "mfma_inst_128_pm1.hip", "mfma_inst_128_u2.hip", "mfma_inst_128_u1.hip", "mfma_inst_128.hip",
-           "mfma_inst_64.hip", "mfma_inst_small.hip", "mfma_inst_small_pair.hip", "mfma_inst_small_matrix.hip", "mfma_inst_32.hip",
+           "mfma_inst_64.hip", "mfma_inst_small.hip", "mfma_inst_small_wide.hip", "mfma_inst_small_pair.hip", "mfma_inst_small_matrix.hip", "mfma_inst_32.hip",
            "tile_inst_8.hip", "tile_inst_4.hip", "tile_inst_2.hip", "layer.hip", "input_layer.hip", "pack.hip", "pool.hip",
            "mfma_inst_256.hip", "common.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra",

@@ -117,7 +117,16 @@ static bool try_mfma(const Problem &pr, MfmaParams &mp, void *stream, int &rc, S
         const int64_t nse = round_up(ceil_div(mp.Kw, 2), 4);          // steps of the small-layer kernel (groups of four)
         mp.nk = 1;
         mp.c0 = (kA == OPK_PM1 && kB == OPK_PM1) ? -static_cast<int>(nse * 64 - pr.Ktotal) : 0;
-        const unsigned g = static_cast<unsigned>(nsplit == 1 ? ceil_div(tiles, 4) : tiles);
+        // Large convolution layers (one wave tile per wave): 32 x 64 wave tiles, so that the row operand is loaded,
+        // decoded and expanded once for 64 output channels.
+        int fn = 1;
+        if (pr.conv && nsplit == 1) fn = pr.N % 64 == 0 ? 2 : 1;
+        if (const char *ef = std::getenv("APNN_MFMA_FN")) {             // 1 | 2 (tests, experiments)
+            const int f = std::atoi(ef);
+            if (f == 1 || (f == 2 && pr.conv && nsplit == 1)) fn = f;
+        }
+        const int64_t wave_tiles = ceil_div(pr.M, 32) * ceil_div(pr.N, 32 * fn);
+        const unsigned g = static_cast<unsigned>(nsplit == 1 ? ceil_div(wave_tiles, 4) : tiles);
         const int gmax = static_cast<int>(ceil_div(nse / 4, nsplit));  // most groups of four steps a wave has
         if (plan) {
             if (pr.conv && nsplit == 4) {
@@ -127,8 +136,10 @@ static bool try_mfma(const Problem &pr, MfmaParams &mp, void *stream, int &rc, S
             rc = APNN_OK;
             return true;
         }
-        ok = pr.conv ? launch_mfma_small_conv(mp, kA, kB, mp.Cw % 4 == 0 ? 4 : 2, nsplit, gmax, g, as_stream(stream))
-                     : launch_mfma_small_matrix(mp, kA, kB, nsplit, g, as_stream(stream));
+        const int vw = mp.Cw % 4 == 0 ? 4 : 2;
+        ok = !pr.conv ? launch_mfma_small_matrix(mp, kA, kB, nsplit, g, as_stream(stream))
+             : fn > 1 ? launch_mfma_small_conv_wide(mp, kA, kB, vw, fn, g, as_stream(stream))
+                      : launch_mfma_small_conv(mp, kA, kB, vw, nsplit, gmax, g, as_stream(stream));
         if (!ok) return false;
         rc = check_launch(pr.who);
         return true;

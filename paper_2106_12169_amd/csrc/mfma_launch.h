@@ -19,6 +19,8 @@ bool launch_mfma32(const MfmaParams &p, int kindA, int kindB, bool conv, unsigne
 // over its waves (grid = tiles).  vw: conv loader vector width in words (4 or 2).
 bool launch_mfma_small_conv(const MfmaParams &p, int kindA, int kindB, int vw, int nsplit, int gmax, unsigned grid,
                             hipStream_t st);
+// One wave tile of 32 x 32 fn outputs per wave, no K split (fn = 2; grid = ceil(row tiles x ceil(N / (32 fn)) / 4)).
+bool launch_mfma_small_conv_wide(const MfmaParams &p, int kindA, int kindB, int vw, int fn, unsigned grid, hipStream_t st);
 // Two convolution layers in one launch (nsplit = 4 both; gmax: the larger of the two, rounded to an instance).
 bool launch_mfma_small_conv_pair(const MfmaParams &p0, unsigned grid0, const MfmaParams &p1, unsigned grid1, int kindA,
                                  int kindB, int vw, int gmax, hipStream_t st);

@@ -18,14 +18,18 @@ def dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
-@pytest.fixture(params=["auto", "pop8", "pop4", "pop2", "mfma32", "mfma32split1", "mfma32split4", "mfma32chunked", "mfma64", "mfma128", "mfma256"])
+@pytest.fixture(params=["auto", "pop8", "pop4", "pop2", "mfma32", "mfma32split1", "mfma32split4", "mfma32split1wide2", "mfma32chunked", "mfma64", "mfma128", "mfma256"])
 def tile(request, monkeypatch):
     """Kernel path under test: the library's own choice, the AND+popcount kernel with
     each register tile, or the FP4 matrix-core kernel with each block tile."""
-    for v in ("APNN_TILE", "APNN_MFMA", "APNN_MFMA_TILE", "APNN_MFMA_SMALL", "APNN_MFMA_NSPLIT"):
+    for v in ("APNN_TILE", "APNN_MFMA", "APNN_MFMA_TILE", "APNN_MFMA_SMALL", "APNN_MFMA_NSPLIT", "APNN_MFMA_FN"):
         monkeypatch.delenv(v, raising=False)
     kind = request.param
-    if kind.startswith("pop"):
+    if kind.startswith("mfma32split1wide"):             # one wave tile of 32 x 64 / 32 x 128 outputs per wave
+        monkeypatch.setenv("APNN_MFMA_TILE", "32")
+        monkeypatch.setenv("APNN_MFMA_NSPLIT", "1")
+        monkeypatch.setenv("APNN_MFMA_FN", kind[-1])
+    elif kind.startswith("pop"):
         monkeypatch.setenv("APNN_MFMA", "0")
         monkeypatch.setenv("APNN_TILE", kind[3:])
     elif kind.startswith("mfma32split"):                # lane-private small-layer kernel, forced K split
@@ -83,16 +87,18 @@ PM1_FEATURE_CONVS = [
 ]
 
 
-@pytest.mark.parametrize("force", ["auto", "64", "32split1", "32split4"])
+@pytest.mark.parametrize("force", ["auto", "64", "32split1", "32split4", "32split1wide2"])
 @pytest.mark.parametrize("Cin,Cout,H,Wd,R,stride,pad,encW,p,BS", PM1_FEATURE_CONVS)
 def test_conv_with_pm1_features_matches_oracle(monkeypatch, force, Cin, Cout, H, Wd, R, stride, pad, encW, p, BS):
     """-1/+1 features (Case II and the mirrored Case III) with zero-contribution padding."""
-    for v in ("APNN_TILE", "APNN_MFMA", "APNN_MFMA_TILE", "APNN_MFMA_SMALL", "APNN_MFMA_NSPLIT"):
+    for v in ("APNN_TILE", "APNN_MFMA", "APNN_MFMA_TILE", "APNN_MFMA_SMALL", "APNN_MFMA_NSPLIT", "APNN_MFMA_FN"):
         monkeypatch.delenv(v, raising=False)
     if force != "auto":
         monkeypatch.setenv("APNN_MFMA_TILE", force[:2])
         if force.startswith("32split"):
-            monkeypatch.setenv("APNN_MFMA_NSPLIT", force[-1])
+            monkeypatch.setenv("APNN_MFMA_NSPLIT", force[7])
+        if "wide" in force:                             # 32 x 64 / 32 x 128 wave tiles
+            monkeypatch.setenv("APNN_MFMA_FN", force[-1])
     Wv = wl.operand(41 + Cin + Cout, Cout, Cin * R * R, p, encW).reshape(Cout, Cin, R, R)
     Xv = wl.fair_signs(42 + H, (BS, Cin, H, Wd))
     d = B.Conv(BS, H, Wd, Cin, Cout, R, R, stride, pad, p, 1, encW, P)
@@ -294,7 +300,7 @@ def test_patch_packer_geometries(C, H, W, R, S, stride, pad, bits):
     assert (words[:, :, R:] == 0).all()
 
 
-@pytest.mark.parametrize("force", ["auto", "64", "32split1", "32split4"])
+@pytest.mark.parametrize("force", ["auto", "64", "32split1", "32split4", "32split1wide2"])
 @pytest.mark.parametrize("mode", [B.POOL_MAX2, B.POOL_SUM2])
 @pytest.mark.parametrize("BS,Cin,Cout,H,Wd,R,stride,pad,with_res", [
     (2, 64, 64, 14, 14, 3, 1, 1, False),
@@ -304,12 +310,14 @@ def test_patch_packer_geometries(C, H, W, R, S, stride, pad, bits):
 ])
 def test_fused_pooling_matches_oracle(monkeypatch, force, mode, BS, Cin, Cout, H, Wd, R, stride, pad, with_res):
     """conv -> 2 x 2 grid pooling of the int32 results -> scale/bias (+ residual) -> requantise -> repack, one kernel."""
-    for v in ("APNN_TILE", "APNN_MFMA", "APNN_MFMA_TILE", "APNN_MFMA_SMALL", "APNN_MFMA_NSPLIT"):
+    for v in ("APNN_TILE", "APNN_MFMA", "APNN_MFMA_TILE", "APNN_MFMA_SMALL", "APNN_MFMA_NSPLIT", "APNN_MFMA_FN"):
         monkeypatch.delenv(v, raising=False)
     if force != "auto":
         monkeypatch.setenv("APNN_MFMA_TILE", force[:2])
         if force.startswith("32split"):
-            monkeypatch.setenv("APNN_MFMA_NSPLIT", force[-1])
+            monkeypatch.setenv("APNN_MFMA_NSPLIT", force[7])
+        if "wide" in force:                             # 32 x 64 / 32 x 128 wave tiles
+            monkeypatch.setenv("APNN_MFMA_FN", force[-1])
     Wv = wl.fair_signs(71 + Cin, (Cout, Cin, R, R))
     Xv = wl.uniform_codes(72 + H, (BS, Cin, H, Wd), 2)
     d = B.Conv(BS, H, Wd, Cin, Cout, R, R, stride, pad, 1, 2, P, U)

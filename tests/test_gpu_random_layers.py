@@ -14,9 +14,9 @@ from tests import helpers as hp
 
 pytestmark = pytest.mark.gpu
 U, P = B.ENC_UNSIGNED, B.ENC_PM1
-ENV = ("APNN_TILE", "APNN_MFMA", "APNN_MFMA_TILE", "APNN_MFMA_SMALL", "APNN_MFMA_NSPLIT", "APNN_MFMA_SHORTK")
+ENV = ("APNN_TILE", "APNN_MFMA", "APNN_MFMA_TILE", "APNN_MFMA_SMALL", "APNN_MFMA_NSPLIT", "APNN_MFMA_SHORTK", "APNN_MFMA_FN")
 OUTCOMES = []          # (seed, "computed" | "refused") of this process's sweep
-FORCES = ("auto", "auto", "auto", "64", "32split1", "32split4", "32chunked", "pop4", "pop2", "128")
+FORCES = ("auto", "auto", "auto", "64", "32split1", "32split4", "32chunked", "pop4", "pop2", "128", "32split1wide2")
 
 
 def dev(a):
@@ -34,7 +34,9 @@ def _force(monkeypatch, force):
         monkeypatch.setenv("APNN_MFMA_SMALL", "0")
     elif force.startswith("32split"):
         monkeypatch.setenv("APNN_MFMA_TILE", "32")
-        monkeypatch.setenv("APNN_MFMA_NSPLIT", force[-1])
+        monkeypatch.setenv("APNN_MFMA_NSPLIT", force[7])
+        if "wide" in force:
+            monkeypatch.setenv("APNN_MFMA_FN", force[-1])
     elif force != "auto":
         monkeypatch.setenv("APNN_MFMA_TILE", force)
 
