@@ -382,8 +382,9 @@ extern "C" int apnn_layer_pair(const apnn_layer_desc *descA, const uint32_t *WA_
     SmallPlan a{}, b{};
     if (int rc = layer_impl(who, *descA, WA_dev, XA_dev, outA_packed_dev, stream, &a)) return rc;
     if (int rc = layer_impl(who, *descB, WB_dev, XB_dev, outB_packed_dev, stream, &b)) return rc;
+    // (sharing pays while the layers are bound by launch and drain: up to a few blocks per compute unit)
     if (a.ok && b.ok && a.kA == b.kA && a.kB == b.kB && a.vw == b.vw &&
-        static_cast<uint64_t>(a.grid) + b.grid <= 0x7FFFFFFFu) {
+        static_cast<uint64_t>(a.grid) + b.grid <= 2048u) {
         const int gmax = (a.gmax <= 1 && b.gmax <= 1) ? 1 : 5;
         if (launch_mfma_small_conv_pair(a.mp, a.grid, b.mp, b.grid, a.kA, a.kB, a.vw, gmax, as_stream(stream)))
             return check_launch(who);
