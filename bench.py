@@ -70,6 +70,7 @@ def main():
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--network-only", type=int, default=0, metavar="N",
                     help="run only N eager forward passes of the ResNet-18-shaped network (for rocprofv3 kernel traces)")
+    ap.add_argument("--network-batch", type=int, default=8, metavar="B", help="batch size of --network-only")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch one 256 MiB apnn_probe_copy (reference for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -89,8 +90,8 @@ def main():
     if args.network_only > 0:
         from paper_2106_12169_amd.network import PackedNet
         layers = wl.resnet18_layers()
-        net = PackedNet(layers, wl.network_params(layers), 8)
-        img = dev(wl.image_batch(2004, 8, 224))
+        net = PackedNet(layers, wl.network_params(layers), args.network_batch)
+        img = dev(wl.image_batch(2004, args.network_batch, 224))
         for _ in range(args.network_only):
             net.forward(img)
         torch.cuda.synchronize()
