@@ -7,8 +7,9 @@ convolution, then the fused scale/bias(+residual) -> floor -> clamp step
 its residual network, so the wiring used here (identity or 1x1-conv shortcut
 codes added inside the second conv's epilogue, max pooling on codes, global
 sum pooling, a final fully connected layer with int32 logits and no
-requantisation) is this build's reading: parity unpinned beyond the pins of
-the individual functions.
+requantisation) is this build's reading.  Pinned node by node (source and
+residual nodes, pooling, operand orientation of the last layer) against a
+layer table written out in tests/test_oracle_network_pins.py.
 """
 
 from __future__ import annotations

@@ -20,9 +20,10 @@
  * Pin status: orc_gemm, orc_conv2d, orc_apbit_gemm, orc_quantize,
  * orc_epilogue, orc_fold_bn, orc_maxpool, orc_sumpool, orc_gridpool are pinned by the
  * non-GPU tests (printed examples of Sec. 3.2, closed forms, brute force,
- * float64 library cross-checks).  The residual-network wiring built from
- * them in the tests is "parity unpinned": the paper gives no layer list for
- * it, so the chained oracle defines it.
+ * float64 library cross-checks).  The chain built from them (network.py) is
+ * pinned node by node against a layer table written out in its test and
+ * against library pooling / float64 products; the residual wiring itself is
+ * this build's reading, since the paper prints no layer list (Sec. 5.1).
  */
 #ifndef APNN_ORACLE_H
 #define APNN_ORACLE_H
