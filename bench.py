@@ -114,7 +114,8 @@ def main():
 
     if args.copy_probe:
         src = torch.zeros(1 << 28, dtype=torch.uint8, device="cuda")
-        B.apnn_probe_copy(src, torch.empty_like(src))
+        from paper_2106_12169_amd import bench_probes
+        bench_probes.apnn_probe_copy(src, torch.empty_like(src))
     def timed(steps, warmup):
         for _ in range(warmup):
             step()
@@ -131,13 +132,12 @@ def main():
         return (t1 - t0) / steps, float(kern.mean())
 
     # headline: the library's own dispatch (FP4 matrix-core kernel for <= 2-bit operands)
-    os.environ.pop("APNN_MFMA", None)
     sec_per_step, gemm_s = timed(args.steps, args.warmup)
     flops = wk.effective_ops                                       # 2 M N K multiply-adds on the matrix cores
     # the AND + popcount kernel on the same workload (the VALU bitwise+popcount roofline)
-    os.environ["APNN_MFMA"] = "0"
+    B.apnn_debug_force("MFMA", 0)
     _, pop_s = timed(max(args.steps // 4, 5), max(args.warmup // 4, 2))
-    os.environ.pop("APNN_MFMA", None)
+    B.apnn_debug_reset()
     step()                                                         # leave the default path's result in Y
     torch.cuda.synchronize()
     lane_ops = 2.0 * wk.M * wk.N * wk.K * wk.p * wk.q / 32.0     # AND + popcount-accumulate per 32 bit-products
@@ -293,9 +293,9 @@ def extra_configs(B, wl, dev, graph_time):
         B.apnn_pack_patches(img, L.R, L.S, L.stride, L.pad, L.q, out=patches)
         B.apnn_layer(dg, Wpp, patches, is_gemm=True, q_out=L.q_out, scale=sc1, bias=bi1, out=out1)
     t_fp4 = graph_time(planes_form)
-    os.environ["APNN_MFMA"] = "0"
+    B.apnn_debug_force("MFMA", 0)
     t_pop = graph_time(planes_form)
-    del os.environ["APNN_MFMA"]
+    B.apnn_debug_reset()
     ex["config4_input_layer_us"] = {"int8_matrix_instruction_from_image": round(t_i8 * 1e6, 2),
                                     "patch_planes_fp4_matrix_kernel": round(t_fp4 * 1e6, 2),
                                     "patch_planes_and_popcount_kernel": round(t_pop * 1e6, 2)}

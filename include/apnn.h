@@ -82,7 +82,8 @@ size_t apnn_fmap_words(int64_t pixels, int64_t C, int bits);
 
 /* ---- bit decomposition and packing (Sec. 3.1 Eq. 2, Sec. 4.2 (a)) -------- */
 
-/* src_dev: rows x K values, one per byte, row-major.  UNSIGNED: uint8 in
+/* src_dev: rows x K values, one per byte, row-major.  The encoding fixes how a
+ * byte is read (no separate signedness argument): UNSIGNED: uint8 in
  * [0, 2^bits) (higher bits are ignored).  PM1: int8 -1/+1 (bit = value > 0).
  * dst_dev: matrix layout, apnn_packed_words(rows, K, bits) words, fully
  * written (pad words zeroed). */
@@ -188,6 +189,12 @@ typedef struct {
 int apnn_layer(const apnn_layer_desc *desc, const uint32_t *W_dev, const uint32_t *X_dev,
                uint32_t *out_packed_dev, void *stream);
 
+/* Device scratch memory apnn_layer / apnn_layer_pair / apnn_input_layer would
+ * need for `desc`, for the caller to allocate: always 0.  Every reduction of the
+ * kernels (K split over the waves of a block, the row-sum term of Sec. 3.2
+ * Case III) happens in registers and LDS, so no entry point takes a workspace. */
+size_t apnn_workspace_bytes(const apnn_layer_desc *desc);
+
 /* Two layers that do not depend on each other (neither reads what the other
  * writes), e.g. the 3 x 3 convolution and the 1 x 1 shortcut convolution of a
  * down-sampling residual block (Sec. 5.1): same arguments, checks and results as
@@ -214,8 +221,8 @@ int apnn_pack_input_weights(const void *src_dev, int64_t Cout, int64_t Cin, int 
                             apnn_encoding enc, void *dst_dev, void *stream);
 
 /* Y[n][ho][wo][co] as in apnn_conv2d for image_dev = N x Cin x H x W unsigned
- * bytes (any Cin >= 1; conv.q is the number of significant bits, conv.encX must
- * be APNN_ENC_UNSIGNED), W_dev from apnn_pack_input_weights, then the epilogue and
+ * bytes (any Cin >= 1; conv.q is the number of significant bits, higher bits of a
+ * byte are ignored; conv.encX must be APNN_ENC_UNSIGNED), W_dev from apnn_pack_input_weights, then the epilogue and
  * the outputs of apnn_layer (acc_out_dev, float_out_dev, residual, q_out planes in
  * [pixel][q_out][Cout/32]).  desc->is_gemm and desc->pool must be 0.
  * APNN_ERR_UNSUPPORTED unless S <= 8, W >= 8, p <= 7, Cout <= 128 and
@@ -242,16 +249,6 @@ int apnn_maxpool(const uint32_t *X_dev, int64_t N, int64_t H, int64_t W, int64_t
  * a matrix operand [N][out_bits][apnn_row_words(C)]. */
 int apnn_sumpool(const uint32_t *X_dev, int64_t N, int64_t H, int64_t W, int64_t C, int bits,
                  int out_bits, uint32_t *out_dev, void *stream);
-
-/* ---- measurement helpers --------------------------------------------------- */
-
-/* Register-only AND + popcount-accumulate chain: every lane of `blocks` x 256
- * threads issues 2*iters*unroll lane-operations; the per-lane checksums go to
- * out_dev (blocks*256 words).  *lane_ops receives the lane-operation count of
- * the launch.  Used to measure the sustained bitwise+popcount issue rate. */
-int apnn_probe_valu(int blocks, int iters, uint32_t *out_dev, double *lane_ops, void *stream);
-/* Plain 16-byte-per-lane copy of `bytes` (multiple of 16) from src to dst. */
-int apnn_probe_copy(const void *src_dev, void *dst_dev, size_t bytes, void *stream);
 
 #ifdef __cplusplus
 }

@@ -28,7 +28,8 @@ EXPORTS = (
     "apnn_pack", "apnn_pack_fmap", "apnn_pack_conv_weights", "apnn_pack_patches",
     "apnn_pack_patch_weights", "apnn_quantize", "apnn_gemm", "apnn_conv2d", "apnn_layer",
     "apnn_layer_pair", "apnn_input_weight_bytes", "apnn_pack_input_weights", "apnn_input_layer",
-    "apnn_fold_bn", "apnn_maxpool", "apnn_sumpool", "apnn_probe_valu", "apnn_probe_copy",
+    "apnn_fold_bn", "apnn_maxpool", "apnn_sumpool", "apnn_workspace_bytes",
+    "apnn_debug_force", "apnn_debug_reset",
 )
 
 
@@ -87,11 +88,14 @@ def lib():
     L.apnn_fold_bn.argtypes = [vp, vp, vp, vp, C.c_double, C.c_double, C.c_double, i64, vp, vp]
     L.apnn_maxpool.argtypes = [vp, i64, i64, i64, i64, i32, i32, i32, i32, vp, vp]
     L.apnn_sumpool.argtypes = [vp, i64, i64, i64, i64, i32, i32, vp, vp]
-    L.apnn_probe_valu.argtypes = [i32, i32, vp, C.POINTER(C.c_double), vp]
-    L.apnn_probe_copy.argtypes = [vp, vp, C.c_size_t, vp]
+    L.apnn_workspace_bytes.restype = C.c_size_t
+    L.apnn_workspace_bytes.argtypes = [C.POINTER(LayerDesc)]
+    L.apnn_debug_force.argtypes = [C.c_char_p, i32]
+    L.apnn_debug_reset.restype = None
+    L.apnn_debug_reset.argtypes = []
     for name in EXPORTS:
         if name not in ("apnn_last_error", "apnn_row_words", "apnn_packed_words", "apnn_fmap_words",
-                        "apnn_input_weight_bytes"):
+                        "apnn_input_weight_bytes", "apnn_workspace_bytes", "apnn_debug_reset"):
             getattr(L, name).restype = i32
     _lib = L
     return L
@@ -312,11 +316,15 @@ def apnn_fold_bn(gamma, beta, mean, var, eps: float, zero: float, step: float):
     return scale, bias
 
 
-def apnn_probe_valu(blocks: int, iters: int, out: torch.Tensor) -> float:
-    ops = C.c_double(0.0)
-    _check(lib().apnn_probe_valu(blocks, iters, _ptr(out), C.byref(ops), _stream()))
-    return ops.value
+def apnn_workspace_bytes(d: Conv, *, is_gemm: bool = False, q_out: int = 0, pool: int = 0) -> int:
+    L = LayerDesc(d.c(), int(is_gemm), q_out, None, None, None, 0, 0.0, None, None, pool)
+    return lib().apnn_workspace_bytes(C.byref(L))
 
 
-def apnn_probe_copy(src: torch.Tensor, dst: torch.Tensor):
-    _check(lib().apnn_probe_copy(_ptr(src), _ptr(dst), src.numel() * src.element_size(), _stream()))
+def apnn_debug_force(name: str, value: int) -> None:
+    """Force a kernel choice (include/apnn_debug.h); value < 0 clears it."""
+    _check(lib().apnn_debug_force(name.encode(), int(value)))
+
+
+def apnn_debug_reset() -> None:
+    lib().apnn_debug_reset()

@@ -1,4 +1,4 @@
-"""Build libapnn.so (the C-ABI library) for gfx950 with hipcc, in-tree.
+"""Build libapnn.so (the C-ABI library) and libapnn_bench.so (measurement probes) for gfx950 with hipcc, in-tree.
 
     python -m paper_2106_12169_amd.build        # incremental
     python -m paper_2106_12169_amd.build -f     # rebuild everything
@@ -18,6 +18,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(CSRC, "_build")
 LIB = os.path.join(HERE, "libapnn.so")
+BENCH_LIB = os.path.join(HERE, "libapnn_bench.so")
+BENCH_SOURCES = ["bench_probes.hip"]
 
 # slowest translation units first, so that the parallel build is not left waiting for them
 SOURCES = ["mfma_inst_256_pm1.hip", "mfma_inst_256_u2.hip", "mfma_inst_256_u1.hip",
@@ -32,7 +34,8 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextr
 
 def _deps_mtime() -> float:
     hdrs = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")]
-    hdrs.append(os.path.join(HERE, "..", "include", "apnn.h"))
+    inc = os.path.join(HERE, "..", "include")
+    hdrs += [os.path.join(inc, f) for f in os.listdir(inc) if f.endswith(".h")]
     return max(os.path.getmtime(h) for h in hdrs)
 
 
@@ -56,10 +59,11 @@ def _compile(src: str, force: bool, extra) -> str:
 def build(force: bool = False, extra=()) -> str:
     os.makedirs(OBJ, exist_ok=True)
     with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
-        objs = list(ex.map(lambda s: _compile(s, force, list(extra)), SOURCES))
-    if (force or not os.path.exists(LIB)
-            or os.path.getmtime(LIB) < max(os.path.getmtime(o) for o in objs)):
-        subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB])
+        objs = list(ex.map(lambda s: _compile(s, force, list(extra)), SOURCES + BENCH_SOURCES))
+    for lib, members in ((LIB, objs[:len(SOURCES)]), (BENCH_LIB, objs[len(SOURCES):])):
+        if (force or not os.path.exists(lib)
+                or os.path.getmtime(lib) < max(os.path.getmtime(o) for o in members)):
+            subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", *members, "-o", lib])
     return LIB
 
 

@@ -31,6 +31,7 @@ struct InputParams {
     const int32_t *cterm;   // Cout: 128 * sum of the row's weights
     int C, Kp, KS, nseg;    // channels, bytes per weight row, steps of 32 bytes, K segments C * R
     float invR;
+    uint32_t xmask;         // (2^q - 1) in every byte: image bits above the q significant ones are ignored
 };
 
 // One wave per 32-pixel row tile, all NT column tiles of 32 channels; steps of 32 K bytes:
@@ -104,10 +105,14 @@ template <int NT> __global__ __launch_bounds__(256, NT <= 2 ? 4 : 2) void input_
 #pragma unroll
         for (int g = 0; g < GS; ++g) {
             if (s0 + g < q.KS) {
-                const uint64_t v0 = ((xa[g][0] << shl) >> shr) ^ 0x8080808080808080ull;
-                const uint64_t v1 = ((xa[g][1] << shl) >> shr) ^ 0x8080808080808080ull;
-                const v4i_t a = {static_cast<int>(v0), static_cast<int>(v0 >> 32), static_cast<int>(v1),
-                                 static_cast<int>(v1 >> 32)};
+                // (x & mask) ^ 0x80 per byte as one three-input bit operation (truth table a:0xF0, b:0xCC, c:0xAA)
+                constexpr int AND_XOR = (0xF0 & 0xCC) ^ 0xAA;
+                const uint64_t v0 = (xa[g][0] << shl) >> shr, v1 = (xa[g][1] << shl) >> shr;
+                auto signed_bytes = [&](uint32_t x) {
+                    return static_cast<int>(__builtin_amdgcn_bitop3_b32(x, q.xmask, 0x80808080u, AND_XOR));
+                };
+                const v4i_t a = {signed_bytes(static_cast<uint32_t>(v0)), signed_bytes(static_cast<uint32_t>(v0 >> 32)),
+                                 signed_bytes(static_cast<uint32_t>(v1)), signed_bytes(static_cast<uint32_t>(v1 >> 32))};
 #pragma unroll
                 for (int j = 0; j < NT; ++j) acc[j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, wb[g][j], acc[j], 0, 0, 0);
             }
@@ -368,6 +373,7 @@ extern "C" int apnn_input_layer(const apnn_layer_desc *desc, const void *W_dev, 
     q.KS = q.Kp / 32;
     q.nseg = static_cast<int>(d.Cin) * d.R;
     q.invR = 1.0f / static_cast<float>(d.R);
+    q.xmask = 0x01010101u * ((1u << d.q) - 1u);
     q.w = static_cast<const int8_t *>(W_dev);
     q.cterm = reinterpret_cast<const int32_t *>(q.w + round_up(N * q.Kp, 16));
     const unsigned grid = static_cast<unsigned>(ceil_div(M, 128));

@@ -1,22 +1,48 @@
 // Host side of apnn_gemm / apnn_conv2d / apnn_layer: argument validation,
 // encoding recovery constants (Sec. 3.2), tile choice (Sec. 4.3) and launch.
+#include <atomic>
 #include <cstdlib>
+#include <cstring>
 
+#include "../../include/apnn_debug.h"
 #include "common.h"
 #include "mfma_launch.h"
 #include "tile_launch.h"
 
 namespace apnn {
 
+// Kernel-choice overrides (tests, experiments).  Each is read from the process
+// environment once, the first time any of them is asked for, and can afterwards be
+// set or cleared through apnn_debug_force; the dispatch itself only loads an int.
+enum Override { OV_MFMA, OV_TILE, OV_MFMA_TILE, OV_MFMA_SHORTK, OV_MFMA_SMALL, OV_MFMA_NSPLIT, OV_MFMA_FN, OV_INT8, OV_COUNT };
+static const char *const kOverrideNames[OV_COUNT] = {"MFMA", "TILE", "MFMA_TILE", "MFMA_SHORTK", "MFMA_SMALL",
+                                                     "MFMA_NSPLIT", "MFMA_FN", "INT8"};
+static std::atomic<int> g_override[OV_COUNT];
+
+static void overrides_from_env()
+{
+    for (int i = 0; i < OV_COUNT; ++i) {
+        char name[40] = "APNN_";
+        std::strncat(name, kOverrideNames[i], sizeof(name) - 6);
+        const char *e = std::getenv(name);
+        g_override[i].store(e && *e ? std::atoi(e) : -1, std::memory_order_relaxed);
+    }
+}
+
+// Value of an override, -1 when it is not set.
+static int ov(Override which)
+{
+    static const bool once = (overrides_from_env(), true);
+    (void)once;
+    return g_override[which].load(std::memory_order_relaxed);
+}
+
 // Tile choice in the spirit of Sec. 4.3 (thread-level parallelism first, then
 // compute intensity), with the constants re-fitted to 256 compute units.
-// APNN_TILE=8|4|2 overrides the choice (experiments, tests).
+// The TILE override (8, 4 or 2) replaces the choice (experiments, tests).
 static int pick_tile(int64_t M, int64_t N)
 {
-    if (const char *e = std::getenv("APNN_TILE")) {
-        const int r = std::atoi(e);
-        if (r == 8 || r == 4 || r == 2) return r;
-    }
+    if (const int r = ov(OV_TILE); r == 8 || r == 4 || r == 2) return r;
     // Measured on MI355X: the 64 x 64 tile (4 waves per SIMD) matches or beats the
     // 128 x 128 tile (2 waves per SIMD) from 1024^2 outputs up, because the extra
     // resident waves cover block start-up and drain; below one block per compute
@@ -37,7 +63,7 @@ struct Problem {
 // Applies when every partial sum stays an exact fp32 integer
 // (K max|a| max|b| < 2^24), the encodings are ones the kernel has a digit kind
 // for, and (convolution) the channel count allows 8-byte loader vectors.
-// APNN_MFMA=0 forces the AND+popcount kernel (the literal AP-Bit emulation).
+// The MFMA override set to 0 forces the AND+popcount kernel (the literal AP-Bit emulation).
 static bool mfma_kind(int planes, apnn_encoding enc, int &kind, int &digits, int64_t &maxabs)
 {
     if (enc == APNN_ENC_PM1) { kind = OPK_PM1; digits = 1; maxabs = 1; return planes == 1; }
@@ -49,10 +75,7 @@ static bool mfma_kind(int planes, apnn_encoding enc, int &kind, int &digits, int
 
 static int pick_mfma_tile(int64_t M, int64_t N, bool conv)
 {
-    if (const char *e = std::getenv("APNN_MFMA_TILE")) {
-        const int t = std::atoi(e);
-        if (t == 32 || t == 64 || t == 128 || (t == 256 && !conv)) return t;
-    }
+    if (const int t = ov(OV_MFMA_TILE); t == 32 || t == 64 || t == 128 || (t == 256 && !conv)) return t;
     // largest block tile that still gives most of the 256 compute units a block and
     // wastes at most a quarter of its area on the ragged edges
     auto tiles = [&](int t) { return ceil_div(M, t) * ceil_div(N, t); };
@@ -81,8 +104,7 @@ struct SmallPlan {
 // launched: the plan is filled in if the layer takes the small-layer convolution kernel, and left not ok otherwise.
 static bool try_mfma(const Problem &pr, MfmaParams &mp, void *stream, int &rc, SmallPlan *plan)
 {
-    const char *e = std::getenv("APNN_MFMA");
-    if (e && std::atoi(e) == 0) return false;
+    if (ov(OV_MFMA) == 0) return false;
     int kA, kB;
     int64_t maxA, maxB;
     if (!mfma_kind(pr.PA, pr.encA, kA, mp.DA, maxA) || !mfma_kind(pr.PB, pr.encB, kB, mp.DB, maxB)) return false;
@@ -99,8 +121,8 @@ static bool try_mfma(const Problem &pr, MfmaParams &mp, void *stream, int &rc, S
         const int64_t lim = int64_t(1) << 31;
         if (4 * pr.M * pr.PA * mp.ldwA >= lim || 4 * pr.N * pr.PB * mp.ldwB >= lim || 4 * (pr.M + 256) * pr.N >= lim) t = 64;
     }
-    const char *esk = std::getenv("APNN_MFMA_SHORTK");           // 0: no special case for short K (experiments)
-    const bool short_k = !pr.conv && mp.Kw <= 8 && t <= 64 && !(esk && std::atoi(esk) == 0);   // 8-word chunks: no step multiplies padding
+    // 8-word chunks: no step multiplies padding (override 0: no special case for short K)
+    const bool short_k = !pr.conv && mp.Kw <= 8 && t <= 64 && ov(OV_MFMA_SHORTK) != 0;
     if (short_k) t = 64;
     const int kc = short_k ? 8 : mfma_chunk_words(t);
     mp.nk = static_cast<int>(ceil_div(mp.Kw, kc));
@@ -109,11 +131,9 @@ static bool try_mfma(const Problem &pr, MfmaParams &mp, void *stream, int &rc, S
     if (tiles > 0x7FFFFFFF) return false;
     const unsigned grid = static_cast<unsigned>(tiles);
     bool ok;
-    const char *es = std::getenv("APNN_MFMA_SMALL");                   // 0: chunked kernel also for small layers (tests)
-    if (t == 32 && !(es && std::atoi(es) == 0)) {                      // small layer: lane-private loads, no LDS staging
-        const char *en = std::getenv("APNN_MFMA_NSPLIT");
+    if (t == 32 && ov(OV_MFMA_SMALL) != 0) {                           // small layer: lane-private loads, no LDS staging (0: chunked kernel)
         int nsplit = tiles <= 4096 ? 4 : 1;                            // measured: the split wins up to a few thousand tiles
-        if (en && (std::atoi(en) == 1 || std::atoi(en) == 4)) nsplit = std::atoi(en);
+        if (const int en = ov(OV_MFMA_NSPLIT); en == 1 || en == 4) nsplit = en;
         const int64_t nse = round_up(ceil_div(mp.Kw, 2), 4);          // steps of the small-layer kernel (groups of four)
         mp.nk = 1;
         mp.c0 = (kA == OPK_PM1 && kB == OPK_PM1) ? -static_cast<int>(nse * 64 - pr.Ktotal) : 0;
@@ -121,10 +141,7 @@ static bool try_mfma(const Problem &pr, MfmaParams &mp, void *stream, int &rc, S
         // decoded and expanded once for 64 output channels.
         int fn = 1;
         if (pr.conv && nsplit == 1) fn = pr.N % 64 == 0 ? 2 : 1;
-        if (const char *ef = std::getenv("APNN_MFMA_FN")) {             // 1 | 2 (tests, experiments)
-            const int f = std::atoi(ef);
-            if (f == 1 || (f == 2 && pr.conv && nsplit == 1)) fn = f;
-        }
+        if (const int f = ov(OV_MFMA_FN); f == 1 || (f == 2 && pr.conv && nsplit == 1)) fn = f;   // (tests, experiments)
         const int64_t wave_tiles = ceil_div(pr.M, 32) * ceil_div(pr.N, 32 * fn);
         const unsigned g = static_cast<unsigned>(nsplit == 1 ? ceil_div(wave_tiles, 4) : tiles);
         const int gmax = static_cast<int>(ceil_div(nse / 4, nsplit));  // most groups of four steps a wave has
@@ -391,4 +408,29 @@ extern "C" int apnn_layer_pair(const apnn_layer_desc *descA, const uint32_t *WA_
     }
     if (int rc = layer_impl(who, *descA, WA_dev, XA_dev, outA_packed_dev, stream)) return rc;
     return layer_impl(who, *descB, WB_dev, XB_dev, outB_packed_dev, stream);
+}
+
+extern "C" int apnn_debug_force(const char *name, int value)
+{
+    clear_error();
+    if (!name) return fail(APNN_ERR_INVALID_ARG, "apnn_debug_force: name is null");
+    (void)ov(OV_MFMA);                                   // the environment is read before the first explicit setting
+    for (int i = 0; i < OV_COUNT; ++i)
+        if (std::strcmp(name, kOverrideNames[i]) == 0) {
+            g_override[i].store(value < 0 ? -1 : value, std::memory_order_relaxed);
+            return APNN_OK;
+        }
+    return fail(APNN_ERR_INVALID_ARG, "apnn_debug_force: unknown override '%s'", name);
+}
+
+extern "C" void apnn_debug_reset(void)
+{
+    (void)ov(OV_MFMA);
+    overrides_from_env();
+}
+
+extern "C" size_t apnn_workspace_bytes(const apnn_layer_desc *desc)
+{
+    (void)desc;
+    return 0;
 }

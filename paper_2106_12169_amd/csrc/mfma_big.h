@@ -21,8 +21,9 @@
 //     after each matrix instruction of step s, each fenced against instruction
 //     scheduling; shifts work on the words of two consecutive steps at once
 //     (64-bit shifts: the bits that cross between the words fall outside the masks);
-//   - the int32 output is stored straight from the accumulators with range-checked
-//     buffer stores (two 128-byte row segments per instruction, no branches, no waits).
+//   - the int32 output is stored straight from the accumulators with buffer stores whose
+//     per-lane offset carries row and column, so the hardware's range check drops what
+//     lies beyond M x N (two 128-byte row segments per instruction, no branches, no waits).
 #pragma once
 #include "mfma_kernel.h"
 
@@ -420,10 +421,12 @@ __global__ __launch_bounds__(64 * NWM * NWN, FM * FN >= 16 ? 1 : 2) void mfma_bi
     if (p.Y && !p.scale) {
         // Plain int32 output, straight from the accumulators: register r of tile (i, j)
         // is row 8 (r / 4) + 4 lh + r % 4, column lr, so one store instruction writes two
-        // whole 128-byte row segments.  Buffer stores: rows beyond M fall outside the
-        // descriptor and are dropped by the hardware, columns beyond N are sent out of
-        // range explicitly; no branches, no waits, the stores stream out behind the
-        // conversions.  The host guarantees (M + BM) N 4 < 2^31.
+        // whole 128-byte row segments.  Buffer stores with the whole byte offset (row and
+        // column) in the per-lane offset, the only part the hardware checks against the
+        // descriptor's size: rows beyond M land beyond the M x N bytes and are dropped,
+        // columns beyond N are sent out of range explicitly; no branches, no waits, the
+        // stores stream out behind the conversions.  The host guarantees (M + BM) N 4 < 2^31,
+        // so adding a row offset never carries into the out-of-range bit.
         const __amdgpu_buffer_rsrc_t rsrcY =
             __builtin_amdgcn_make_buffer_rsrc(p.Y, 0, 4u * static_cast<uint32_t>(p.M) * p.N, 0x00020000);
         const int gn0 = n0 + wn * FN * 32 + lr;
@@ -434,7 +437,8 @@ __global__ __launch_bounds__(64 * NWM * NWN, FM * FN >= 16 ? 1 : 2) void mfma_bi
         static_for<FM * FN * 16>([&](auto c) {
             constexpr int i = decltype(c)::value / (FN * 16), j = decltype(c)::value / 16 % FN, r = decltype(c)::value % 16;
             constexpr int row = i * 32 + 8 * (r >> 2) + (r & 3);
-            __builtin_amdgcn_raw_buffer_store_b32(static_cast<int>(acc[i][j][r]) + p.c0, rsrcY, voffY[j], 4 * row * p.N, 0);
+            __builtin_amdgcn_raw_buffer_store_b32(static_cast<int>(acc[i][j][r]) + p.c0, rsrcY,
+                                                  voffY[j] + 4u * row * static_cast<uint32_t>(p.N), 0, 0);
         });
         return;
     }

@@ -1,4 +1,4 @@
-// Pooling on packed codes (Sec. 5.2) and the measurement probes.
+// Pooling on packed codes (Sec. 5.2).
 #include "common.h"
 
 namespace apnn {
@@ -121,48 +121,6 @@ __global__ __launch_bounds__(64 * NWAVE) void sumpool_kernel(const uint32_t *__r
     }
 }
 
-// Register-only AND + popcount-accumulate chain on an 8 x 8 accumulator tile.
-__global__ __launch_bounds__(256) void probe_valu_kernel(uint32_t *__restrict__ out, int iters)
-{
-    uint32_t a[8], b[8], acc[8][8];
-    const uint32_t seed = blockIdx.x * 256u + threadIdx.x;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        a[i] = seed * 2654435761u + i * 40503u;
-        b[i] = ~seed * 2246822519u + i * 9176u;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) acc[i][j] = 0;
-    }
-    for (int it = 0; it < iters; ++it) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            uint32_t t0, t1, t2, t3, t4, t5, t6, t7;
-            asm volatile(
-                "v_and_b32 %0, %16, %17\n\tv_and_b32 %1, %16, %18\n\tv_and_b32 %2, %16, %19\n\tv_and_b32 %3, %16, %20\n\t"
-                "v_and_b32 %4, %16, %21\n\tv_and_b32 %5, %16, %22\n\tv_and_b32 %6, %16, %23\n\tv_and_b32 %7, %16, %24\n\t"
-                "v_bcnt_u32_b32 %8, %0, %8\n\tv_bcnt_u32_b32 %9, %1, %9\n\tv_bcnt_u32_b32 %10, %2, %10\n\t"
-                "v_bcnt_u32_b32 %11, %3, %11\n\tv_bcnt_u32_b32 %12, %4, %12\n\tv_bcnt_u32_b32 %13, %5, %13\n\t"
-                "v_bcnt_u32_b32 %14, %6, %14\n\tv_bcnt_u32_b32 %15, %7, %15"
-                : "=&v"(t0), "=&v"(t1), "=&v"(t2), "=&v"(t3), "=&v"(t4), "=&v"(t5), "=&v"(t6), "=&v"(t7),
-                  "+v"(acc[i][0]), "+v"(acc[i][1]), "+v"(acc[i][2]), "+v"(acc[i][3]), "+v"(acc[i][4]),
-                  "+v"(acc[i][5]), "+v"(acc[i][6]), "+v"(acc[i][7])
-                : "v"(a[i]), "v"(b[0]), "v"(b[1]), "v"(b[2]), "v"(b[3]), "v"(b[4]), "v"(b[5]), "v"(b[6]), "v"(b[7]));
-        }
-    }
-    uint32_t s = 0;
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-#pragma unroll
-        for (int j = 0; j < 8; ++j) s += acc[i][j];
-    out[blockIdx.x * 256 + threadIdx.x] = s;
-}
-
-__global__ __launch_bounds__(256) void probe_copy_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst, size_t n)
-{
-    const size_t stride = static_cast<size_t>(gridDim.x) * 256;
-    for (size_t i = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x; i < n; i += stride) dst[i] = src[i];
-}
-
 }  // namespace apnn
 
 using namespace apnn;
@@ -215,26 +173,4 @@ extern "C" int apnn_sumpool(const uint32_t *X_dev, int64_t N, int64_t H, int64_t
         hipLaunchKernelGGL(sumpool_kernel<16>, grid, dim3(1024), 0, as_stream(stream), X_dev, out_dev,
                            static_cast<int>(H * W), static_cast<int>(C), Cw, bits, out_bits, ldw);
     return check_launch("apnn_sumpool");
-}
-
-extern "C" int apnn_probe_valu(int blocks, int iters, uint32_t *out_dev, double *lane_ops, void *stream)
-{
-    clear_error();
-    if (blocks < 1 || iters < 1 || !out_dev) return fail(APNN_ERR_INVALID_ARG, "apnn_probe_valu: bad argument");
-    hipLaunchKernelGGL(probe_valu_kernel, dim3(blocks), dim3(256), 0, as_stream(stream), out_dev, iters);
-    if (lane_ops) *lane_ops = 128.0 * iters * 256.0 * blocks;   // 64 AND + 64 popcount-accumulate per iteration
-    return check_launch("apnn_probe_valu");
-}
-
-extern "C" int apnn_probe_copy(const void *src_dev, void *dst_dev, size_t bytes, void *stream)
-{
-    clear_error();
-    if (!src_dev || !dst_dev || bytes % 16 != 0) return fail(APNN_ERR_INVALID_ARG, "apnn_probe_copy: bad argument");
-    if (!aligned16(src_dev) || !aligned16(dst_dev)) return fail(APNN_ERR_ALIGNMENT, "apnn_probe_copy: buffers must be 16-byte aligned");
-    if (bytes == 0) return APNN_OK;
-    const size_t n = bytes / 16;
-    const unsigned grid = static_cast<unsigned>(n / 256 + 1 < 8192 ? n / 256 + 1 : 8192);
-    hipLaunchKernelGGL(probe_copy_kernel, dim3(grid), dim3(256), 0, as_stream(stream),
-                       static_cast<const uint4 *>(src_dev), static_cast<uint4 *>(dst_dev), n);
-    return check_launch("apnn_probe_copy");
 }

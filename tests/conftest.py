@@ -15,3 +15,12 @@ def pytest_configure(config):
 @pytest.fixture(scope="session")
 def golden_dir():
     return os.path.join(ROOT, "tests", "golden")
+
+
+@pytest.fixture(autouse=True)
+def _kernel_choice_back_to_default():
+    """Tests force kernel choices through apnn_debug_force; none of them leaks into the next test."""
+    yield
+    from paper_2106_12169_amd import binding
+    if binding._lib is not None:
+        binding.apnn_debug_reset()

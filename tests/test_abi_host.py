@@ -15,13 +15,38 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 FAKE = 0x10000          # a 16-byte aligned non-null "device pointer" that must never be dereferenced
 
 
+def _declared(*headers):
+    out = set()
+    for h in headers:
+        text = re.sub(r"/\*.*?\*/", "", open(os.path.join(ROOT, "include", h)).read(), flags=re.S)
+        out |= set(re.findall(r"\b(apnn_[a-z0-9_]+)\s*\(", text))
+    return out
+
+
 def test_library_exports_every_declared_symbol():
-    hdr = open(os.path.join(ROOT, "include", "apnn.h")).read()
-    declared = set(re.findall(r"\b(apnn_[a-z0-9_]+)\s*\(", hdr))
+    from paper_2106_12169_amd import bench_probes as BP
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["apnn.h", "apnn_bench.h", "apnn_debug.h"]
+    declared = _declared("apnn.h", "apnn_debug.h")
     assert declared == set(B.EXPORTS), declared ^ set(B.EXPORTS)
     L = C.CDLL(B.LIB_PATH)
     for name in declared:
         assert hasattr(L, name), name
+    probes = _declared("apnn_bench.h")
+    assert probes == set(BP.EXPORTS)
+    LB = C.CDLL(BP.LIB_PATH)
+    for name in probes:
+        assert hasattr(LB, name) and not hasattr(L, name), name
+
+
+def test_workspace_is_never_needed_and_overrides_are_host_only():
+    assert B.apnn_workspace_bytes(B.Conv(8, 28, 28, 128, 128, 3, 3, 1, 1), q_out=2) == 0
+    assert B.lib().apnn_workspace_bytes(None) == 0
+    B.apnn_debug_force("MFMA", 0)
+    B.apnn_debug_force("MFMA", -1)
+    with pytest.raises(B.ApnnError) as ei:
+        B.apnn_debug_force("NO_SUCH_SWITCH", 1)
+    assert ei.value.status == 1
+    B.apnn_debug_reset()
 
 
 def test_sizes():

@@ -44,6 +44,22 @@ def test_input_layer_accumulators(C, H, W, R, S, stride, pad, bits, Cout, p, enc
     assert np.array_equal(acc.cpu().numpy().transpose(0, 3, 1, 2), want)
 
 
+@pytest.mark.parametrize("bits", [1, 3, 5, 7])
+def test_input_layer_ignores_image_bits_above_q(bits):
+    """conv.q is the number of significant image bits: bytes with higher bits set give the product of the low
+    `bits` bits, as the plane packers do (they ignore higher bits as well)."""
+    BS, C, H, W, Cout = 2, 3, 20, 37, 64
+    raw = wl.uniform_codes(310 + bits, (BS, C, H, W), 8)
+    assert (raw >> bits).max() > 0
+    low = (raw & ((1 << bits) - 1)).astype(np.uint8)
+    Wv = wl.fair_signs(410 + bits, (Cout, C, 5, 5))
+    d = B.Conv(BS, H, W, C, Cout, 5, 5, 2, 2, 1, bits, P, U)
+    acc = torch.empty((BS, d.Ho, d.Wo, Cout), dtype=torch.int32, device="cuda")
+    B.apnn_input_layer(d, B.apnn_pack_input_weights(dev(Wv), 1, P), dev(raw), acc_out=acc)
+    torch.cuda.synchronize()
+    assert np.array_equal(acc.cpu().numpy().transpose(0, 3, 1, 2), oracle.conv2d(Wv, P, 1, low, U, bits, 2, 2))
+
+
 @pytest.mark.parametrize("q_out,with_res", [(2, False), (2, True), (1, False), (8, False)])
 def test_input_layer_fused_epilogue(q_out, with_res):
     BS, HW, Cout = 2, 38, 64

@@ -22,24 +22,23 @@ def dev(a):
 def tile(request, monkeypatch):
     """Kernel path under test: the library's own choice, the AND+popcount kernel with
     each register tile, or the FP4 matrix-core kernel with each block tile."""
-    for v in ("APNN_TILE", "APNN_MFMA", "APNN_MFMA_TILE", "APNN_MFMA_SMALL", "APNN_MFMA_NSPLIT", "APNN_MFMA_FN"):
-        monkeypatch.delenv(v, raising=False)
+    B.apnn_debug_reset()
     kind = request.param
     if kind.startswith("mfma32split1wide"):             # one wave tile of 32 x 64 / 32 x 128 outputs per wave
-        monkeypatch.setenv("APNN_MFMA_TILE", "32")
-        monkeypatch.setenv("APNN_MFMA_NSPLIT", "1")
-        monkeypatch.setenv("APNN_MFMA_FN", kind[-1])
+        B.apnn_debug_force("MFMA_TILE", 32)
+        B.apnn_debug_force("MFMA_NSPLIT", 1)
+        B.apnn_debug_force("MFMA_FN", int(kind[-1]))
     elif kind.startswith("pop"):
-        monkeypatch.setenv("APNN_MFMA", "0")
-        monkeypatch.setenv("APNN_TILE", kind[3:])
+        B.apnn_debug_force("MFMA", 0)
+        B.apnn_debug_force("TILE", int(kind[3:]))
     elif kind.startswith("mfma32split"):                # lane-private small-layer kernel, forced K split
-        monkeypatch.setenv("APNN_MFMA_TILE", "32")
-        monkeypatch.setenv("APNN_MFMA_NSPLIT", kind[-1])
+        B.apnn_debug_force("MFMA_TILE", 32)
+        B.apnn_debug_force("MFMA_NSPLIT", int(kind[-1]))
     elif kind == "mfma32chunked":                      # K-split tile with the chunked loop instead of the resident one
-        monkeypatch.setenv("APNN_MFMA_TILE", "32")
-        monkeypatch.setenv("APNN_MFMA_SMALL", "0")
+        B.apnn_debug_force("MFMA_TILE", 32)
+        B.apnn_debug_force("MFMA_SMALL", 0)
     elif kind.startswith("mfma"):
-        monkeypatch.setenv("APNN_MFMA_TILE", kind[4:])
+        B.apnn_debug_force("MFMA_TILE", int(kind[4:]))
     return kind
 
 
@@ -91,14 +90,13 @@ PM1_FEATURE_CONVS = [
 @pytest.mark.parametrize("Cin,Cout,H,Wd,R,stride,pad,encW,p,BS", PM1_FEATURE_CONVS)
 def test_conv_with_pm1_features_matches_oracle(monkeypatch, force, Cin, Cout, H, Wd, R, stride, pad, encW, p, BS):
     """-1/+1 features (Case II and the mirrored Case III) with zero-contribution padding."""
-    for v in ("APNN_TILE", "APNN_MFMA", "APNN_MFMA_TILE", "APNN_MFMA_SMALL", "APNN_MFMA_NSPLIT", "APNN_MFMA_FN"):
-        monkeypatch.delenv(v, raising=False)
+    B.apnn_debug_reset()
     if force != "auto":
-        monkeypatch.setenv("APNN_MFMA_TILE", force[:2])
+        B.apnn_debug_force("MFMA_TILE", int(force[:2]))
         if force.startswith("32split"):
-            monkeypatch.setenv("APNN_MFMA_NSPLIT", force[7])
+            B.apnn_debug_force("MFMA_NSPLIT", int(force[7]))
         if "wide" in force:                             # 32 x 64 / 32 x 128 wave tiles
-            monkeypatch.setenv("APNN_MFMA_FN", force[-1])
+            B.apnn_debug_force("MFMA_FN", int(force[-1]))
     Wv = wl.operand(41 + Cin + Cout, Cout, Cin * R * R, p, encW).reshape(Cout, Cin, R, R)
     Xv = wl.fair_signs(42 + H, (BS, Cin, H, Wd))
     d = B.Conv(BS, H, Wd, Cin, Cout, R, R, stride, pad, p, 1, encW, P)
@@ -128,12 +126,12 @@ def test_binary_network_chain():
 def test_conv_with_pm1_features_refused_without_matrix_path(monkeypatch):
     """The AND+popcount kernel has no zero-contribution padding for -1/+1 features: the call must fail, not be wrong."""
     e = torch.zeros(1 << 16, dtype=torch.int32, device="cuda")
-    monkeypatch.setenv("APNN_MFMA", "0")
+    B.apnn_debug_force("MFMA", 0)
     for d in (B.Conv(1, 8, 8, 64, 32, 3, 3, 1, 1, 1, 1, P, P), B.Conv(1, 8, 8, 64, 32, 3, 3, 1, 1, 2, 1, U, P)):
         with pytest.raises(B.ApnnError) as ei:
             B.apnn_conv2d(d, e, e)
         assert ei.value.status == 2
-    monkeypatch.delenv("APNN_MFMA")
+    B.apnn_debug_force("MFMA", -1)
     with pytest.raises(B.ApnnError) as ei:                      # one channel word: not a matrix-core shape
         B.apnn_conv2d(B.Conv(1, 8, 8, 32, 32, 3, 3, 1, 1, 1, 1, P, P), e, e)
     assert ei.value.status == 2
@@ -310,14 +308,13 @@ def test_patch_packer_geometries(C, H, W, R, S, stride, pad, bits):
 ])
 def test_fused_pooling_matches_oracle(monkeypatch, force, mode, BS, Cin, Cout, H, Wd, R, stride, pad, with_res):
     """conv -> 2 x 2 grid pooling of the int32 results -> scale/bias (+ residual) -> requantise -> repack, one kernel."""
-    for v in ("APNN_TILE", "APNN_MFMA", "APNN_MFMA_TILE", "APNN_MFMA_SMALL", "APNN_MFMA_NSPLIT", "APNN_MFMA_FN"):
-        monkeypatch.delenv(v, raising=False)
+    B.apnn_debug_reset()
     if force != "auto":
-        monkeypatch.setenv("APNN_MFMA_TILE", force[:2])
+        B.apnn_debug_force("MFMA_TILE", int(force[:2]))
         if force.startswith("32split"):
-            monkeypatch.setenv("APNN_MFMA_NSPLIT", force[7])
+            B.apnn_debug_force("MFMA_NSPLIT", int(force[7]))
         if "wide" in force:                             # 32 x 64 / 32 x 128 wave tiles
-            monkeypatch.setenv("APNN_MFMA_FN", force[-1])
+            B.apnn_debug_force("MFMA_FN", int(force[-1]))
     Wv = wl.fair_signs(71 + Cin, (Cout, Cin, R, R))
     Xv = wl.uniform_codes(72 + H, (BS, Cin, H, Wd), 2)
     d = B.Conv(BS, H, Wd, Cin, Cout, R, R, stride, pad, 1, 2, P, U)
@@ -353,7 +350,7 @@ def test_fused_pooling_refusals(monkeypatch):
     with pytest.raises(B.ApnnError) as ei:                      # GEMM layers have no frame to pool
         B.apnn_layer(B.Conv(8, 1, 1, 64, 64, 1, 1, 1, 0, 1, 2, P, U), e, e, is_gemm=True, q_out=2, scale=f, bias=f, pool=1)
     assert ei.value.status == 1
-    monkeypatch.setenv("APNN_MFMA", "0")                        # the AND+popcount kernel does not pool
+    B.apnn_debug_force("MFMA", 0)                        # the AND+popcount kernel does not pool
     with pytest.raises(B.ApnnError) as ei:
         B.apnn_layer(d, e, e, q_out=2, scale=f, bias=f, pool=1)
     assert ei.value.status == 2
@@ -364,10 +361,9 @@ def test_fused_pooling_refusals(monkeypatch):
 def test_fused_gemm_layer_all_matrix_tiles(monkeypatch, force, q, q_out, with_res):
     """Fully-connected layer with the whole epilogue (scale/bias, residual, requantise, repack, int32 and fp32 side
     outputs) through every matrix-operand kernel, the large-tile one included; ragged batch."""
-    for v in ("APNN_TILE", "APNN_MFMA", "APNN_MFMA_TILE", "APNN_MFMA_SMALL", "APNN_MFMA_NSPLIT"):
-        monkeypatch.delenv(v, raising=False)
+    B.apnn_debug_reset()
     if force != "auto":
-        monkeypatch.setenv("APNN_MFMA_TILE", force)
+        B.apnn_debug_force("MFMA_TILE", int(force))
     BS, K, Cout = 600, 1000, 320
     Xv = wl.uniform_codes(81 + q, (BS, K), q)
     Wv = wl.fair_signs(82, (Cout, K))

@@ -19,14 +19,14 @@ def dev(a):
 
 @pytest.fixture(autouse=True, params=["32", "32split1", "32split4", "32chunked", "64", "128", "256"])
 def mfma_tile(request, monkeypatch):
-    monkeypatch.delenv("APNN_MFMA", raising=False)
-    monkeypatch.delenv("APNN_MFMA_SMALL", raising=False)
-    monkeypatch.setenv("APNN_MFMA_TILE", request.param[:2] if request.param.startswith("32") else request.param)
-    monkeypatch.delenv("APNN_MFMA_NSPLIT", raising=False)
+    B.apnn_debug_force("MFMA", -1)
+    B.apnn_debug_force("MFMA_SMALL", -1)
+    B.apnn_debug_force("MFMA_TILE", int(request.param[:2] if request.param.startswith("32") else request.param))
+    B.apnn_debug_force("MFMA_NSPLIT", -1)
     if request.param == "32chunked":
-        monkeypatch.setenv("APNN_MFMA_SMALL", "0")
+        B.apnn_debug_force("MFMA_SMALL", 0)
     if request.param.startswith("32split"):
-        monkeypatch.setenv("APNN_MFMA_NSPLIT", request.param[-1])
+        B.apnn_debug_force("MFMA_NSPLIT", int(request.param[-1]))
 
 
 def gpu_gemm(W, encW, p, X, encX, q):

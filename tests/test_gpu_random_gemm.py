@@ -12,7 +12,6 @@ from paper_2106_12169_amd import workloads as wl
 
 pytestmark = pytest.mark.gpu
 U, P = B.ENC_UNSIGNED, B.ENC_PM1
-ENV = ("APNN_TILE", "APNN_MFMA", "APNN_MFMA_TILE", "APNN_MFMA_SMALL", "APNN_MFMA_NSPLIT", "APNN_MFMA_SHORTK")
 FORCES = ("auto", "auto", "256", "256", "128", "128", "64", "32split1", "32split4", "32chunked", "pop8", "pop4", "pop2")
 
 
@@ -24,19 +23,18 @@ def dev(a):
 def test_random_gemm(monkeypatch, seed):
     rng = np.random.default_rng(9000 + seed)
     force = FORCES[rng.integers(len(FORCES))]
-    for v in ENV:
-        monkeypatch.delenv(v, raising=False)
+    B.apnn_debug_reset()
     if force.startswith("pop"):
-        monkeypatch.setenv("APNN_MFMA", "0")
-        monkeypatch.setenv("APNN_TILE", force[3:])
+        B.apnn_debug_force("MFMA", 0)
+        B.apnn_debug_force("TILE", int(force[3:]))
     elif force == "32chunked":
-        monkeypatch.setenv("APNN_MFMA_TILE", "32")
-        monkeypatch.setenv("APNN_MFMA_SMALL", "0")
+        B.apnn_debug_force("MFMA_TILE", 32)
+        B.apnn_debug_force("MFMA_SMALL", 0)
     elif force.startswith("32split"):
-        monkeypatch.setenv("APNN_MFMA_TILE", "32")
-        monkeypatch.setenv("APNN_MFMA_NSPLIT", force[-1])
+        B.apnn_debug_force("MFMA_TILE", 32)
+        B.apnn_debug_force("MFMA_NSPLIT", int(force[-1]))
     elif force != "auto":
-        monkeypatch.setenv("APNN_MFMA_TILE", force)
+        B.apnn_debug_force("MFMA_TILE", int(force))
     M, N = int(rng.integers(1, 420)), int(rng.integers(1, 420))
     K = int(rng.choice([rng.integers(1, 70), rng.integers(70, 700), rng.integers(700, 2100)]))
     encW, p = (P, 1) if rng.integers(2) else (U, int(rng.integers(1, 9)))

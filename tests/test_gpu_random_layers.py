@@ -14,7 +14,6 @@ from tests import helpers as hp
 
 pytestmark = pytest.mark.gpu
 U, P = B.ENC_UNSIGNED, B.ENC_PM1
-ENV = ("APNN_TILE", "APNN_MFMA", "APNN_MFMA_TILE", "APNN_MFMA_SMALL", "APNN_MFMA_NSPLIT", "APNN_MFMA_SHORTK", "APNN_MFMA_FN")
 OUTCOMES = []          # (seed, "computed" | "refused") of this process's sweep
 FORCES = ("auto", "auto", "auto", "64", "32split1", "32split4", "32chunked", "pop4", "pop2", "128", "32split1wide2")
 
@@ -24,21 +23,20 @@ def dev(a):
 
 
 def _force(monkeypatch, force):
-    for v in ENV:
-        monkeypatch.delenv(v, raising=False)
+    B.apnn_debug_reset()
     if force.startswith("pop"):
-        monkeypatch.setenv("APNN_MFMA", "0")
-        monkeypatch.setenv("APNN_TILE", force[3:])
+        B.apnn_debug_force("MFMA", 0)
+        B.apnn_debug_force("TILE", int(force[3:]))
     elif force == "32chunked":
-        monkeypatch.setenv("APNN_MFMA_TILE", "32")
-        monkeypatch.setenv("APNN_MFMA_SMALL", "0")
+        B.apnn_debug_force("MFMA_TILE", 32)
+        B.apnn_debug_force("MFMA_SMALL", 0)
     elif force.startswith("32split"):
-        monkeypatch.setenv("APNN_MFMA_TILE", "32")
-        monkeypatch.setenv("APNN_MFMA_NSPLIT", force[7])
+        B.apnn_debug_force("MFMA_TILE", 32)
+        B.apnn_debug_force("MFMA_NSPLIT", int(force[7]))
         if "wide" in force:
-            monkeypatch.setenv("APNN_MFMA_FN", force[-1])
+            B.apnn_debug_force("MFMA_FN", int(force[-1]))
     elif force != "auto":
-        monkeypatch.setenv("APNN_MFMA_TILE", force)
+        B.apnn_debug_force("MFMA_TILE", int(force))
 
 
 def _draw(rng):
