@@ -91,6 +91,58 @@ static int pick_mfma_tile(int64_t M, int64_t N, bool conv)
     return 32;                                  // small layers: one wave tile per block, K split over its waves
 }
 
+// ---- 8-bit integer matrix path (matrix operands) -------------------------------------
+// One pass over K whatever p and q are (the FP4 form needs ceil(p/2) ceil(q/2)), exact for every K the int32
+// result allows.  Taken when the FP4 form would need three or more passes and the product has enough 128 x 128
+// tiles to occupy the chip, or when the FP4 form could not be exact.  Override INT8: 0 never, 1 whenever it applies.
+struct I8Operand { int cls; int alpha, off, flipped, pad; uint32_t flip; };
+
+static I8Operand i8_operand(int planes, apnn_encoding enc)
+{
+    I8Operand o{};
+    o.cls = planes <= 2 ? 0 : planes <= 4 ? 1 : 2;
+    if (enc == APNN_ENC_PM1) {            // the stored bit b stands for 2 b - 1
+        o.alpha = 2; o.off = -1;
+    } else if (planes == 8) {             // the byte is value - 128 (top plane inverted)
+        o.alpha = 1; o.off = 128; o.flipped = 128; o.pad = -128; o.flip = ~0u;
+    } else {
+        o.alpha = 1;
+    }
+    return o;
+}
+
+static bool try_int8(const Problem &pr, MfmaParams &mp, bool fp4_exact, void *stream, int &rc)
+{
+    const int force = ov(OV_INT8);
+    if (force == 0 || ov(OV_MFMA) == 0 || pr.conv || pr.Ktotal <= 0) return false;
+    const int64_t tiles = ceil_div(pr.M, 128) * ceil_div(pr.N, 128);
+    if (force != 1) {
+        const int passes = ((pr.PA + 1) / 2) * ((pr.PB + 1) / 2);
+        if (fp4_exact && (passes < 3 || tiles < 64)) return false;
+    }
+    const int64_t lim = int64_t(1) << 31;       // operands and output are addressed with 31-bit byte offsets
+    if (4 * pr.M * pr.PA * mp.ldwA >= lim || 4 * pr.N * pr.PB * mp.ldwB >= lim || 4 * (pr.M + 128) * pr.N >= lim) return false;
+    if (tiles > 0x7FFFFFFF) return false;
+    const I8Operand a = i8_operand(pr.PA, pr.encA), b = i8_operand(pr.PB, pr.encB);
+    mp.PA = pr.PA; mp.PB = pr.PB;
+    mp.nk = static_cast<int>(ceil_div(mp.Kw, 4));
+    const int64_t K = pr.Ktotal, npad = static_cast<int64_t>(mp.nk) * 128 - K;
+    mp.flipA = a.flip; mp.flipB = b.flip;
+    mp.accmul = a.alpha * b.alpha;
+    mp.mulA = a.alpha * b.off;
+    mp.mulB = b.alpha * a.off;
+    // (wrapping 32-bit arithmetic, as in the kernel: the terms cancel to a result that fits)
+    mp.c0 = static_cast<int>(static_cast<uint32_t>(-static_cast<int64_t>(a.alpha) * b.alpha * npad * a.pad * b.pad
+                                                   - static_cast<int64_t>(a.alpha) * b.off * a.flipped * K
+                                                   - static_cast<int64_t>(b.alpha) * a.off * b.flipped * K
+                                                   + K * a.off * b.off));
+    mp.out_scale = 1.0f;
+    mp.xcd_regions = (ceil_div(pr.M, 128) % 2 == 0 && ceil_div(pr.N, 128) % 4 == 0) ? 1 : 0;
+    if (!launch_mfma_i8(mp, a.cls, b.cls, static_cast<unsigned>(tiles), as_stream(stream))) return false;
+    rc = check_launch(pr.who);
+    return true;
+}
+
 // What the dispatch decided for a layer that takes the small-layer convolution kernel with K split over the
 // waves of a block: filled in instead of launching when a caller wants to put two such layers into one launch.
 struct SmallPlan {
@@ -109,7 +161,9 @@ static bool try_mfma(const Problem &pr, MfmaParams &mp, void *stream, int &rc, S
     int64_t maxA, maxB;
     if (!mfma_kind(pr.PA, pr.encA, kA, mp.DA, maxA) || !mfma_kind(pr.PB, pr.encB, kB, mp.DB, maxB)) return false;
     // (a pooled sum adds four results before the conversion to an integer)
-    if (pr.Ktotal <= 0 || round_up(pr.Ktotal, 1024) * maxA * maxB * (mp.pool == 2 ? 4 : 1) >= (int64_t(1) << 24)) return false;
+    const bool fp4_exact = pr.Ktotal > 0 && round_up(pr.Ktotal, 1024) * maxA * maxB * (mp.pool == 2 ? 4 : 1) < (int64_t(1) << 24);
+    if (!plan && try_int8(pr, mp, fp4_exact, stream, rc)) return true;
+    if (!fp4_exact) return false;
     if (pr.conv && mp.Cw % 2 != 0) return false;
     if (pr.conv && kA == OPK_PM1) kA = OPK_PM1Z;         // -1/+1 features: taps outside the frame must contribute 0
     mp.PA = pr.PA; mp.PB = pr.PB;

@@ -92,6 +92,10 @@ struct MfmaParams {
     uint32_t *out;
     int q_out;
     int NW;
+    // 8-bit integer matrix form only (mfma_i8_kernel): Y = accmul acc + mulA RA[row] + mulB RB[column] + c0, RA / RB
+    // the decoded row sums of the operands; flipA / flipB invert the top plane of an 8-plane operand (value - 128)
+    uint32_t flipA, flipB;
+    int accmul, mulA, mulB;
 };
 
 // A 32-bit constant the optimiser cannot fold: it then lives in a register, so

@@ -26,6 +26,9 @@ bool launch_mfma_small_conv_pair(const MfmaParams &p0, unsigned grid0, const Mfm
                                  int kindB, int vw, int gmax, hipStream_t st);
 bool launch_mfma_small_matrix(const MfmaParams &p, int kindA, int kindB, int nsplit, unsigned grid, hipStream_t st);
 
+// 8-bit integer matrix form (matrix operands, 128 x 128 block tile); class: 0, 1, 2 for up to 2, 4, 8 planes.
+bool launch_mfma_i8(const MfmaParams &p, int classA, int classB, unsigned grid, hipStream_t st);
+
 // K words per chunk of each tile size (must match the instances).
 constexpr int mfma_chunk_words(int tile) { return tile == 256 ? 16 : tile == 128 ? 16 : 32; }
 
