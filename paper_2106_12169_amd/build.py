@@ -32,20 +32,24 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextr
          "-ffp-contract=off", "-fno-fast-math"]
 
 
-def _deps_mtime() -> float:
-    hdrs = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")]
-    inc = os.path.join(HERE, "..", "include")
-    hdrs += [os.path.join(inc, f) for f in os.listdir(inc) if f.endswith(".h")]
-    return max(os.path.getmtime(h) for h in hdrs)
+def _newest_dependency(obj: str, path: str) -> float:
+    """Modification time of the newest file the object was built from (the compiler's own dependency list)."""
+    dep = obj + ".d"
+    if not os.path.exists(dep):
+        return float("inf")
+    names = open(dep).read().replace("\\\n", " ").split(":", 1)[-1].split()
+    try:
+        return max(os.path.getmtime(n) for n in names + [path])
+    except OSError:
+        return float("inf")
 
 
 def _compile(src: str, force: bool, extra) -> str:
     obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
     path = os.path.join(CSRC, src)
-    if (not force and os.path.exists(obj)
-            and os.path.getmtime(obj) >= max(os.path.getmtime(path), _deps_mtime())):
+    if not force and os.path.exists(obj) and os.path.getmtime(obj) >= _newest_dependency(obj, path):
         return obj
-    cmd = ["hipcc", "-x", "hip", *FLAGS, *extra, "-c", path, "-o", obj]
+    cmd = ["hipcc", "-x", "hip", *FLAGS, *extra, "-MD", "-MF", obj + ".d", "-c", path, "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     out = "\n".join(l for l in (r.stdout + r.stderr).splitlines()
                     if "packed-fp32-ops" not in l and "is not a recognized feature" not in l)

@@ -125,7 +125,7 @@ static bool try_int8(const Problem &pr, MfmaParams &mp, bool fp4_exact, void *st
     if (tiles > 0x7FFFFFFF) return false;
     const I8Operand a = i8_operand(pr.PA, pr.encA), b = i8_operand(pr.PB, pr.encB);
     mp.PA = pr.PA; mp.PB = pr.PB;
-    mp.nk = static_cast<int>(ceil_div(mp.Kw, 4));
+    mp.nk = static_cast<int>(round_up(ceil_div(mp.Kw, 4), 4));       // chunks of 4 words; the kernel takes four per loop pass
     const int64_t K = pr.Ktotal, npad = static_cast<int64_t>(mp.nk) * 128 - K;
     mp.flipA = a.flip; mp.flipB = b.flip;
     mp.accmul = a.alpha * b.alpha;

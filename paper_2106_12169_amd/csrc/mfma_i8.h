@@ -28,13 +28,18 @@
 // from the plane words they hold anyway (popcount, as in the AND+popcount kernel).
 //
 // Schedule.  Block tile (2 FM 32) x (2 FN 32), 2 x 2 waves, each FM x FN
-// instruction tiles.  K advances in chunks of 4 words (128 positions = 4 instruction
-// steps): global memory -> LDS directly, 16 bytes per lane (one plane row of the
-// chunk), double buffered, the 16-byte pieces XOR-swizzled by row; lane half h of
-// row r reads words 2h, 2h + 1 of every plane of its fragment rows (8-byte LDS
-// reads), transposes them, and the two words give the bytes of steps (0, 1) and
-// (2, 3).  The K order inside a step is free as long as both operands agree: dword j,
-// byte g of a transposed word is the element at bit 8 g + j.
+// instruction tiles, one wave per SIMD.  K advances in chunks of 4 words (128
+// positions = 4 instruction steps) and is fetched in groups of two or four chunks
+// (32 or 64 bytes of every plane row): global memory -> LDS directly, 16 bytes per
+// lane, adjacent lanes taking adjacent pieces of one plane row, two group buffers,
+// one barrier per group, the 16-byte pieces XOR-swizzled by row; lane half h of row r reads words 2h,
+// 2h + 1 of every plane of its fragment rows (8-byte LDS reads) one chunk ahead, and
+// each word, transposed, gives the bytes of two instruction steps.  The kernel is
+// bound by the vector instructions of the transposition (about 20 per matrix
+// instruction), so the matrix instructions of one word are issued between the pieces
+// of the next word's transposition and run underneath them.  The K order inside a
+// step is free as long as both operands agree: dword j, byte g of a transposed word
+// is the element at bit 8 g + j.
 #pragma once
 #include "mfma_big.h"
 
@@ -56,72 +61,94 @@ __device__ __forceinline__ uint32_t bit_select(uint32_t a, uint32_t b, uint32_t 
 
 struct I8Masks { uint32_t m0f, m33, m55, m03; };
 
-// One stage of the bit-matrix transposition on the pair (lo, hi): the D-bit blocks selected by ~m of lo and
-// by m of hi change places.
-template <int D> __device__ __forceinline__ void swap_blocks(uint32_t &lo, uint32_t &hi, uint32_t m)
+// One stage of a bit-matrix transposition on two pairs (a0, b0), (a1, b1): the D-bit blocks selected by ~m of a and
+// by m of b change places.  The two left shifts and the two right shifts are each one 64-bit shift of a register
+// pair (issued at the rate of a 32-bit one); the bits that cross between the halves land where m drops them.
+template <int D> __device__ __forceinline__ void swap_blocks2(uint32_t &a0, uint32_t &b0, uint32_t &a1, uint32_t &b1, uint32_t m)
 {
-    const uint32_t a = lo, b = hi;
-    lo = bit_select(a, b << D, m);
-    hi = bit_select(a >> D, b, m);
+    const uint64_t up = pair_shl<D>(make_pair(b0, b1)), down = pair_shr<D>(make_pair(a0, a1));
+    const uint32_t na0 = bit_select(a0, half_of<0>(up), m), na1 = bit_select(a1, half_of<1>(up), m);
+    b0 = bit_select(half_of<0>(down), b0, m);
+    b1 = bit_select(half_of<1>(down), b1, m);
+    a0 = na0;
+    a1 = na1;
 }
 
 // Plane words w[0 .. slots) of 32 K positions -> 8 dwords of 4 bytes: byte g of d[j] is the element at bit 8 g + j,
-// i.e. sum_s 2^s bit(w[s], 8 g + j).
-template <int C> __device__ __forceinline__ void planes_to_bytes(const uint32_t (&w)[I8Slots<C>::value], const I8Masks &k, uint32_t (&d)[8])
+// i.e. sum_s 2^s bit(w[s], 8 g + j).  Two parts, so that matrix instructions can be issued in between; x carries
+// the state from part 0 to part 1.
+template <int C, int PART>
+__device__ __forceinline__ void planes_to_bytes(const uint32_t (&w)[I8Slots<C>::value], const I8Masks &k, uint32_t (&x)[8], uint32_t (&d)[8])
 {
     if constexpr (C == I8_C8) {
         // 8 x 8 bit-matrix transposition (plane s, bit j of a byte) inside every byte column, three stages
-        uint32_t x[8];
+        if constexpr (PART == 0) {
 #pragma unroll
-        for (int s = 0; s < 8; ++s) x[s] = w[s];
+            for (int s = 0; s < 8; ++s) x[s] = w[s];
+            swap_blocks2<4>(x[0], x[4], x[1], x[5], k.m0f);
+            swap_blocks2<4>(x[2], x[6], x[3], x[7], k.m0f);
+            swap_blocks2<2>(x[0], x[2], x[1], x[3], k.m33);
+        } else {
+            swap_blocks2<2>(x[4], x[6], x[5], x[7], k.m33);
+            swap_blocks2<1>(x[0], x[1], x[2], x[3], k.m55);
+            swap_blocks2<1>(x[4], x[5], x[6], x[7], k.m55);
 #pragma unroll
-        for (int s = 0; s < 4; ++s) swap_blocks<4>(x[s], x[s + 4], k.m0f);
-#pragma unroll
-        for (int s = 0; s < 8; ++s)
-            if ((s & 2) == 0) swap_blocks<2>(x[s], x[s + 2], k.m33);
-#pragma unroll
-        for (int s = 0; s < 8; s += 2) swap_blocks<1>(x[s], x[s + 1], k.m55);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) d[j] = x[j];
+            for (int j = 0; j < 8; ++j) d[j] = x[j];
+        }
     } else if constexpr (C == I8_C4) {
         // 4 x 4 transposition inside every nibble: nibble n of x[i] becomes the value at position 4 n + i; then the
         // nibbles are spread over the bytes
-        uint32_t x[4] = {w[0], w[1], w[2], w[3]};
-        swap_blocks<2>(x[0], x[2], k.m33);
-        swap_blocks<2>(x[1], x[3], k.m33);
-        swap_blocks<1>(x[0], x[1], k.m55);
-        swap_blocks<1>(x[2], x[3], k.m55);
+        if constexpr (PART == 0) {
+            x[0] = w[0]; x[1] = w[1]; x[2] = w[2]; x[3] = w[3];
+            swap_blocks2<2>(x[0], x[2], x[1], x[3], k.m33);
+            swap_blocks2<1>(x[0], x[1], x[2], x[3], k.m55);
+        } else {
+            const uint64_t h01 = pair_shr<4>(make_pair(x[0], x[1])), h23 = pair_shr<4>(make_pair(x[2], x[3]));
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            d[i] = x[i] & k.m0f;
-            d[4 + i] = (x[i] >> 4) & k.m0f;
+            for (int i = 0; i < 4; ++i) d[i] = x[i] & k.m0f;
+            d[4] = half_of<0>(h01) & k.m0f;
+            d[5] = half_of<1>(h01) & k.m0f;
+            d[6] = half_of<0>(h23) & k.m0f;
+            d[7] = half_of<1>(h23) & k.m0f;
         }
     } else {
         // 2 x 2 transposition inside every bit pair: pair t of x0 is the value at position 2 t, of x1 at 2 t + 1
-        uint32_t x0 = w[0], x1 = w[1];
-        swap_blocks<1>(x0, x1, k.m55);
-        d[0] = x0 & k.m03;
-        d[1] = x1 & k.m03;
-        d[2] = (x0 >> 2) & k.m03;
-        d[3] = (x1 >> 2) & k.m03;
-        d[4] = (x0 >> 4) & k.m03;
-        d[5] = (x1 >> 4) & k.m03;
-        d[6] = (x0 >> 6) & k.m03;
-        d[7] = (x1 >> 6) & k.m03;
+        if constexpr (PART == 0) {
+            const uint32_t a = w[0], b = w[1];
+            x[0] = bit_select(a, b << 1, k.m55);
+            x[1] = bit_select(a >> 1, b, k.m55);
+            const uint64_t h = pair_shr<2>(make_pair(x[0], x[1]));
+            d[0] = x[0] & k.m03;
+            d[1] = x[1] & k.m03;
+            d[2] = half_of<0>(h) & k.m03;
+            d[3] = half_of<1>(h) & k.m03;
+        } else {
+            const uint64_t h4 = pair_shr<4>(make_pair(x[0], x[1])), h6 = pair_shr<6>(make_pair(x[0], x[1]));
+            d[4] = half_of<0>(h4) & k.m03;
+            d[5] = half_of<1>(h4) & k.m03;
+            d[6] = half_of<0>(h6) & k.m03;
+            d[7] = half_of<1>(h6) & k.m03;
+        }
     }
 }
 
-template <int CA, int CB, int FM, int FN>
-__global__ __launch_bounds__(256, FM * FN >= 16 ? 1 : 2) void mfma_i8_kernel(const MfmaParams p)
+// Bytes of LDS the kernel needs for PA + PB planes (two group buffers).
+constexpr int mfma_i8_lds_bytes(int PA, int PB, int G) { return 2 * (PA + PB) * 128 * G * 16; }
+
+template <int CA, int CB, int FM, int FN, int G>
+__global__ __launch_bounds__(256, 1) void mfma_i8_kernel(const MfmaParams p)
 {
-    constexpr int SA = I8Slots<CA>::value, SB = I8Slots<CB>::value;     // 16-byte pieces (one per plane) of an LDS row
+    static_assert(G == 2 || G == 4, "a group is two or four chunks");
+    static_assert(FM == 2 && FN == 2, "128 x 128 block tile");
+    constexpr int SA = I8Slots<CA>::value, SB = I8Slots<CB>::value;     // most planes of the class: width of the transposition
     constexpr int BM = 2 * FM * 32, BN = 2 * FN * 32;
-    constexpr int NA = BM * SA / 256, NB = BN * SB / 256;               // load instructions per wave and chunk
-    static_assert(BM * SA % 256 == 0 && BN * SB % 256 == 0, "every wave issues the same number of loads");
-    constexpr int A_WORDS = BM * SA * 4, B_WORDS = BN * SB * 4;
-    __shared__ __attribute__((aligned(1024))) uint32_t smem[2 * (A_WORDS + B_WORDS)];    // A 0, A 1, B 0, B 1
+    constexpr int RB = 64 / G;                          // rows one load instruction covers (G pieces each)
+    constexpr int KK = BM / RB / 4;                     // load instructions per plane, operand and wave
+    // A group buffer holds, for G chunks: A planes [PA][BM rows][G pieces of 16 bytes], then B planes [PB][BN][G].
+    extern __shared__ __attribute__((aligned(1024))) uint32_t smem[];
     typedef __attribute__((address_space(3))) uint32_t *lds_ptr_t;
     const uint32_t smem_base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_ptr_t)smem));
+    const int a_bytes = p.PA * BM * G * 16, buf_bytes = a_bytes + p.PB * BN * G * 16;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -141,45 +168,80 @@ __global__ __launch_bounds__(256, FM * FN >= 16 ? 1 : 2) void mfma_i8_kernel(con
     km.m0f = reg_const(0x0F0F0F0Fu); km.m33 = reg_const(0x33333333u);
     km.m55 = reg_const(0x55555555u); km.m03 = reg_const(0x03030303u);
 
-    // ---- loader.  A wave-wide load deposits 64 pieces contiguously, i.e. 64 / S whole rows of S pieces; the
-    // piece in slot c of row r is plane c ^ swz(r), so that the 8-byte reads of consecutive rows spread over the
-    // banks.  A plane that does not exist, or a chunk beyond K, is sent out of the descriptor's range: zeros.
-    auto swz = [](int r, int S) { return S == 8 ? (r & 7) : S == 4 ? ((r >> 1) & 3) : ((r >> 2) & 1); };
+    // ---- loader.  One load instruction moves the G pieces of RB consecutive rows of one plane: lanes G r' .. G r' +
+    // G - 1 fetch consecutive 16-byte pieces of one plane row, i.e. of one cache line (a first version had every lane
+    // in a line of its own and was bound by the tag look-ups of the first-level cache).  Piece j of row r' lands in
+    // slot j ^ swz(r') of the row, so that the reads of 8 consecutive rows spread over all banks.  The per-lane part
+    // of the byte offset is the same for every instruction; the rest (plane, row block, group) is wave-uniform and
+    // added on, and the whole sum is what the hardware checks against the operand's size: rows beyond M read zeros.
+    auto swz = [](int r) { return G == 4 ? ((r >> 1) & 3) : ((r >> 2) & 1); };
     const uint32_t bytesA = 4u * static_cast<uint32_t>(p.M) * p.PA * p.ldwA, bytesB = 4u * static_cast<uint32_t>(p.N) * p.PB * p.ldwB;
     const v4u_t descA = make_raw_desc(p.A, bytesA), descB = make_raw_desc(p.B, bytesB);
     constexpr uint32_t OUT_OF_RANGE = 0x80000000u;      // operands are smaller than 2 GiB (host check)
-    uint32_t offA[NA], offB[NB];
-#pragma unroll
-    for (int u = 0; u < NA; ++u) {
-        const int L = 64 * (wave * NA + u) + lane, row = L / SA, plane = (L % SA) ^ swz(row, SA);
-        offA[u] = 4u * ((static_cast<uint32_t>(min(m0 + row, p.M - 1)) * p.PA + plane) * p.ldwA) | (plane < p.PA ? 0u : OUT_OF_RANGE);
-    }
-#pragma unroll
-    for (int u = 0; u < NB; ++u) {
-        const int L = 64 * (wave * NB + u) + lane, row = L / SB, plane = (L % SB) ^ swz(row, SB);
-        offB[u] = 4u * ((static_cast<uint32_t>(min(n0 + row, p.N - 1)) * p.PB + plane) * p.ldwB) | (plane < p.PB ? 0u : OUT_OF_RANGE);
-    }
-    auto fetch = [&](int kc, int buf) {                 // chunk kc -> buffer buf
-        const uint32_t dead = 4 * kc < p.Kw ? 0u : OUT_OF_RANGE;
-        const int soff = __builtin_amdgcn_readfirstlane(16 * kc);
-        // (the LDS addresses are wave-uniform; saying so keeps them in scalar registers)
-        const uint32_t ldsA = __builtin_amdgcn_readfirstlane(smem_base + 4 * (buf * A_WORDS + wave * NA * 256));
-        const uint32_t ldsB = __builtin_amdgcn_readfirstlane(smem_base + 4 * (2 * A_WORDS + buf * B_WORDS + wave * NB * 256));
-#pragma unroll
-        for (int u = 0; u < NA; ++u) load_to_lds_16(descA, ldsA + 1024 * u, offA[u] | dead, soff);
-#pragma unroll
-        for (int u = 0; u < NB; ++u) load_to_lds_16(descB, ldsB + 1024 * u, offB[u] | dead, soff);
+    const int ld_row = lane / G, ld_piece = (lane % G) ^ swz(ld_row);
+    const uint32_t lane_offA = 4u * static_cast<uint32_t>(m0 + ld_row) * p.PA * p.ldwA + 16u * ld_piece;
+    const uint32_t lane_offB = 4u * static_cast<uint32_t>(n0 + ld_row) * p.PB * p.ldwB + 16u * ld_piece;
+    // state of the group being requested: per-lane offsets (out of range where its piece lies beyond K), buffer
+    uint32_t gl_offA = 0, gl_offB = 0;
+    uint32_t gl_lds = 0;
+    int gl_k = 0;
+    auto begin_group = [&](int group, uint32_t lds_bytes_base) {
+        const uint32_t dead = 4 * (group * G + ld_piece) < p.Kw ? 0u : OUT_OF_RANGE;
+        gl_offA = lane_offA | dead;
+        gl_offB = lane_offB | dead;
+        gl_lds = lds_bytes_base;
+        gl_k = __builtin_amdgcn_readfirstlane(group * G * 16);
     };
-    constexpr int NLOAD = NA + NB;
-    constexpr int WAIT_PREVIOUS = 0x0F70 | (NLOAD & 0xF) | ((NLOAD >> 4) << 14);   // s_waitcnt vmcnt(NLOAD): all but the newest chunk
-    constexpr int WAIT_ALL = 0x0F70;
+    // load instruction d of the group, 0 <= d < (SA + SB) KK: plane d / KK of A, then of B; skipped for planes that do not exist
+    auto load_one = [&](auto dc) {
+        constexpr int d = decltype(dc)::value;
+        if constexpr (d < SA * KK) {
+            constexpr int s = d / KK, kk = d % KK;
+            if (s < p.PA) {
+                const int b = wave + 4 * kk;            // row block
+                const uint32_t uni = 4u * static_cast<uint32_t>(b * RB * p.PA + s) * p.ldwA + gl_k;
+                load_to_lds_16(descA, __builtin_amdgcn_readfirstlane(gl_lds + (s * (BM / RB) + b) * 1024), gl_offA + uni, 0);
+            }
+        } else {
+            constexpr int s = (d - SA * KK) / KK, kk = (d - SA * KK) % KK;
+            if (s < p.PB) {
+                const int b = wave + 4 * kk;
+                const uint32_t uni = 4u * static_cast<uint32_t>(b * RB * p.PB + s) * p.ldwB + gl_k;
+                load_to_lds_16(descB, __builtin_amdgcn_readfirstlane(gl_lds + a_bytes + (s * (BN / RB) + b) * 1024), gl_offB + uni, 0);
+            }
+        }
+    };
+    constexpr int NLOAD = (SA + SB) * KK;
+    constexpr int WAIT_LOADS = 0x0F70;                  // s_waitcnt vmcnt(0) (expcnt, lgkmcnt untouched)
 
-    // ---- reader: word offsets of (fragment row 0, plane s) of this lane; fragment f is 32 rows further
-    int rdA[SA], rdB[SB];
+    // ---- reader.  Lane (half h, row r) reads words 2h, 2h + 1 of chunk j of plane s of fragment row f at byte
+    //   buffer + ((s BM + tile row) G + (j ^ swz(r))) 16 + 8 h;
+    // the per-lane part (one register per j, rebuilt when the buffer changes) plus a constant that fits the
+    // instruction's offset field.
+    uint32_t rd0A[G], rd0B[G], rdA[G], rdB[G];
 #pragma unroll
-    for (int s = 0; s < SA; ++s) rdA[s] = ((wm * FM * 32 + lr) * SA + (s ^ swz(lr, SA))) * 4 + 2 * lh;
+    for (int j = 0; j < G; ++j) {
+        rd0A[j] = ((wm * FM * 32 + lr) * G + (j ^ swz(lr & (RB - 1)))) * 16 + 8 * lh;
+        rd0B[j] = a_bytes + ((wn * FN * 32 + lr) * G + (j ^ swz(lr & (RB - 1)))) * 16 + 8 * lh;
+    }
+    auto set_read_buffer = [&](uint32_t byte_base) {
 #pragma unroll
-    for (int s = 0; s < SB; ++s) rdB[s] = 2 * A_WORDS + ((wn * FN * 32 + lr) * SB + (s ^ swz(lr, SB))) * 4 + 2 * lh;
+        for (int j = 0; j < G; ++j) { rdA[j] = rd0A[j] + byte_base; rdB[j] = rd0B[j] + byte_base; }
+    };
+    struct Words { uint2 a[FM][SA], b[FN][SB]; };       // this lane's two words of every plane of its fragment rows
+    constexpr int NREAD = FM * SA + FN * SB;
+    // read r of chunk j: (fragment, plane) of A, then of B; words of planes that do not exist stay zero
+    auto read_one = [&](auto jc, auto rc, Words &w) {
+        constexpr int j = decltype(jc)::value, r = decltype(rc)::value;
+        const char *lds = reinterpret_cast<const char *>(smem);
+        if constexpr (r < FM * SA) {
+            constexpr int f = r / SA, s = r % SA;
+            if (s < p.PA) w.a[f][s] = *reinterpret_cast<const uint2 *>(lds + rdA[j] + (s * BM + 32 * f) * G * 16);
+        } else {
+            constexpr int f = (r - FM * SA) / SB, s = (r - FM * SA) % SB;
+            if (s < p.PB) w.b[f][s] = *reinterpret_cast<const uint2 *>(lds + rdB[j] + (s * BN + 32 * f) * G * 16);
+        }
+    };
 
     v16i_t acc[FM][FN];
 #pragma unroll
@@ -194,88 +256,141 @@ __global__ __launch_bounds__(256, FM * FN >= 16 ? 1 : 2) void mfma_i8_kernel(con
 #pragma unroll
     for (int j = 0; j < FN; ++j) rb[j] = 0;
     const bool need_ra = p.mulA != 0, need_rb = p.mulB != 0;
-
-    fetch(0, 0);
-    fetch(1, 1);
-    __builtin_amdgcn_s_waitcnt(WAIT_PREVIOUS);
-    __syncthreads();
-
-    for (int it = 0; it < p.nk; ++it) {
-        const int buf = it & 1;
-        uint2 wa[FM][SA], wb[FN][SB];
-#pragma unroll
-        for (int f = 0; f < FM; ++f)
-#pragma unroll
-            for (int s = 0; s < SA; ++s)
-                wa[f][s] = *reinterpret_cast<const uint2 *>(&smem[buf * A_WORDS + rdA[s] + f * 32 * SA * 4]);
-#pragma unroll
-        for (int f = 0; f < FN; ++f)
-#pragma unroll
-            for (int s = 0; s < SB; ++s)
-                wb[f][s] = *reinterpret_cast<const uint2 *>(&smem[buf * B_WORDS + rdB[s] + f * 32 * SB * 4]);
-        if (CA == I8_C8) {                              // an 8-bit operand enters as value - 128: top plane inverted
-#pragma unroll
-            for (int f = 0; f < FM; ++f) { wa[f][SA - 1].x ^= p.flipA; wa[f][SA - 1].y ^= p.flipA; }
-        }
-        if (CB == I8_C8) {
-#pragma unroll
-            for (int f = 0; f < FN; ++f) { wb[f][SB - 1].x ^= p.flipB; wb[f][SB - 1].y ^= p.flipB; }
-        }
-        __syncthreads();                                // every wave has read buffer buf: it can take chunk it + 2
-        fetch(it + 2, buf);
+    auto row_sums = [&](const Words &w) {               // (before the top plane of an 8-bit operand is inverted)
         if (need_ra) {
 #pragma unroll
             for (int f = 0; f < FM; ++f)
 #pragma unroll
-                for (int s = 0; s < SA; ++s) {
-                    const uint32_t fl = (CA == I8_C8 && s == SA - 1) ? p.flipA : 0u;
-                    ra[f] += static_cast<uint32_t>(__popc(wa[f][s].x ^ fl) + __popc(wa[f][s].y ^ fl)) << s;
-                }
+                for (int s = 0; s < SA; ++s) ra[f] += static_cast<uint32_t>(__popc(w.a[f][s].x) + __popc(w.a[f][s].y)) << s;
         }
         if (need_rb) {
 #pragma unroll
             for (int f = 0; f < FN; ++f)
 #pragma unroll
-                for (int s = 0; s < SB; ++s) {
-                    const uint32_t fl = (CB == I8_C8 && s == SB - 1) ? p.flipB : 0u;
-                    rb[f] += static_cast<uint32_t>(__popc(wb[f][s].x ^ fl) + __popc(wb[f][s].y ^ fl)) << s;
-                }
+                for (int s = 0; s < SB; ++s) rb[f] += static_cast<uint32_t>(__popc(w.b[f][s].x) + __popc(w.b[f][s].y)) << s;
         }
-#pragma unroll
-        for (int e = 0; e < 2; ++e) {                   // word e of the lane's two: instruction steps 2 e, 2 e + 1
-            uint32_t da[FM][8], db[FN][8];
-#pragma unroll
-            for (int f = 0; f < FM; ++f) {
+    };
+    struct Bytes { uint32_t a[FM][8], b[FN][8]; };      // the bytes of two instruction steps (dwords 0-3, 4-7) per fragment
+
+    // One phase: the 2 FM FN matrix instructions of one word (bytes `cur`), each followed by its share of the
+    // transposition of word E of `wsrc` into `nxt` (cut into 2 (FM + FN) pieces) and by whatever memory
+    // instructions `hook` deals to that slot.  A lone wave issues in order: loads and LDS reads issued in a burst
+    // held up the vector instructions behind them, spread out like this they run underneath.
+    constexpr int NMI = 2 * FM * FN, NPART = 2 * (FM + FN);
+    auto phase = [&](const Bytes &cur, const Words &wsrc, auto enc, Bytes &nxt, auto &&hook) {
+        constexpr int E = decltype(enc)::value;
+        uint32_t x[8];
+        auto part = [&](auto pc) {
+            constexpr int pi = decltype(pc)::value, f = pi / 2, half = pi % 2;
+            if constexpr (f < FM) {
                 uint32_t w[SA];
 #pragma unroll
-                for (int s = 0; s < SA; ++s) w[s] = e ? wa[f][s].y : wa[f][s].x;
-                planes_to_bytes<CA>(w, km, da[f]);
-            }
-#pragma unroll
-            for (int f = 0; f < FN; ++f) {
+                for (int s = 0; s < SA; ++s) w[s] = E ? wsrc.a[f][s].y : wsrc.a[f][s].x;
+                if (CA == I8_C8 && half == 0) w[SA - 1] ^= p.flipA;       // an 8-bit operand enters as value - 128
+                planes_to_bytes<CA, half>(w, km, x, nxt.a[f]);
+            } else {
+                constexpr int g = f - FM;
                 uint32_t w[SB];
 #pragma unroll
-                for (int s = 0; s < SB; ++s) w[s] = e ? wb[f][s].y : wb[f][s].x;
-                planes_to_bytes<CB>(w, km, db[f]);
+                for (int s = 0; s < SB; ++s) w[s] = E ? wsrc.b[g][s].y : wsrc.b[g][s].x;
+                if (CB == I8_C8 && half == 0) w[SB - 1] ^= p.flipB;
+                planes_to_bytes<CB, half>(w, km, x, nxt.b[g]);
             }
+        };
+        static_for<NMI>([&](auto qc) {
+            constexpr int q = decltype(qc)::value, h = q / (FM * FN), i = q / FN % FM, j = q % FN;
+            const v4i_t a = {static_cast<int>(cur.a[i][4 * h]), static_cast<int>(cur.a[i][4 * h + 1]),
+                             static_cast<int>(cur.a[i][4 * h + 2]), static_cast<int>(cur.a[i][4 * h + 3])};
+            const v4i_t b = {static_cast<int>(cur.b[j][4 * h]), static_cast<int>(cur.b[j][4 * h + 1]),
+                             static_cast<int>(cur.b[j][4 * h + 2]), static_cast<int>(cur.b[j][4 * h + 3])};
+            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, acc[i][j], 0, 0, 0);
+            static_for<NPART *(q + 1) / NMI - NPART * q / NMI>([&](auto tc) {
+                part(std::integral_constant<int, NPART * q / NMI + decltype(tc)::value>{});
+            });
+            hook(qc);
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    };
+    using E0 = std::integral_constant<int, 0>;
+    using E1 = std::integral_constant<int, 1>;
+
+    // Group g (chunks G g .. G g + G - 1) lives in buffer g mod 2.  The half-iteration of chunk c multiplies chunk c
+    // while it reads the words of chunk c + 1 and transposes the second word of chunk c and the first of chunk c + 1.
+    // In the last half-iteration of group g: group g + 1 has landed (wait, barrier -- the only ones of the group), the
+    // reads move over to its buffer, and group g + 2 is requested into the buffer of group g, whose words every wave
+    // has in registers by then; it is needed a whole group later.  Chunks beyond the last are zeros that nobody multiplies.
+    Words w0, w1;
+    Bytes by0, by1;
 #pragma unroll
-            for (int h = 0; h < 2; ++h)
+    for (int f = 0; f < FM; ++f)
 #pragma unroll
-                for (int i = 0; i < FM; ++i) {
-                    const v4i_t a = {static_cast<int>(da[i][4 * h]), static_cast<int>(da[i][4 * h + 1]),
-                                     static_cast<int>(da[i][4 * h + 2]), static_cast<int>(da[i][4 * h + 3])};
+        for (int s = 0; s < SA; ++s) w0.a[f][s] = w1.a[f][s] = make_uint2(0u, 0u);
 #pragma unroll
-                    for (int j = 0; j < FN; ++j) {
-                        const v4i_t b = {static_cast<int>(db[j][4 * h]), static_cast<int>(db[j][4 * h + 1]),
-                                         static_cast<int>(db[j][4 * h + 2]), static_cast<int>(db[j][4 * h + 3])};
-                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, acc[i][j], 0, 0, 0);
-                    }
-                }
-        }
-        __builtin_amdgcn_s_waitcnt(WAIT_PREVIOUS);      // chunk it + 1 has landed (chunk it + 2 may still fly)
-        __syncthreads();
+    for (int f = 0; f < FN; ++f)
+#pragma unroll
+        for (int s = 0; s < SB; ++s) w0.b[f][s] = w1.b[f][s] = make_uint2(0u, 0u);
+    begin_group(0, smem_base);
+    static_for<NLOAD>([&](auto dc) { load_one(dc); });
+    begin_group(1, smem_base + buf_bytes);
+    static_for<NLOAD>([&](auto dc) { load_one(dc); });
+    __builtin_amdgcn_s_waitcnt(WAIT_LOADS);
+    __syncthreads();
+    uint32_t cur_base = 0;                              // byte offset of the buffer the reads come from
+    set_read_buffer(cur_base);
+    static_for<NREAD>([&](auto rc) { read_one(E0{}, rc, w0); });
+    auto no_hook = [](auto) {};
+    {
+        Bytes dummy;                                    // (the matrix instructions of this warm-up phase multiply zeros into zero accumulators)
+#pragma unroll
+        for (int f = 0; f < FM; ++f)
+#pragma unroll
+            for (int d = 0; d < 8; ++d) dummy.a[f][d] = 0;
+#pragma unroll
+        for (int f = 0; f < FN; ++f)
+#pragma unroll
+            for (int d = 0; d < 8; ++d) dummy.b[f][d] = 0;
+        row_sums(w0);
+        phase(dummy, w0, E0{}, by0, no_hook);
     }
-    __builtin_amdgcn_s_waitcnt(WAIT_ALL);               // the loads issued for chunks beyond the last one have landed
+    auto half_iteration = [&](int group, auto jjc, Words &wc, Words &wn_) {
+        constexpr int jj = decltype(jjc)::value, jn = (jj + 1) % G;     // chunk of the group being multiplied / read
+        constexpr bool LAST = jj == G - 1;
+        if constexpr (LAST) {
+            __builtin_amdgcn_s_waitcnt(WAIT_LOADS);     // this wave's share of group + 1 is in LDS
+            __syncthreads();
+            begin_group(group + 2, smem_base + cur_base);
+            cur_base = cur_base ? 0u : static_cast<uint32_t>(buf_bytes);
+            set_read_buffer(cur_base);
+        }
+        // first phase: the reads of chunk c + 1, and the first half of the group's loads
+        phase(by0, wc, E1{}, by1, [&](auto qc) {
+            constexpr int q = decltype(qc)::value;
+            static_for<NREAD *(q + 1) / NMI - NREAD * q / NMI>([&](auto ic) {
+                read_one(std::integral_constant<int, jn>{}, std::integral_constant<int, NREAD * q / NMI + decltype(ic)::value>{}, wn_);
+            });
+            if constexpr (LAST)
+                static_for<NLOAD *(q + 1) / (2 * NMI) - NLOAD * q / (2 * NMI)>([&](auto ic) {
+                    load_one(std::integral_constant<int, NLOAD * q / (2 * NMI) + decltype(ic)::value>{});
+                });
+        });
+        row_sums(wn_);
+        phase(by1, wn_, E0{}, by0, [&](auto qc) {
+            constexpr int q = decltype(qc)::value + NMI;
+            if constexpr (LAST)
+                static_for<NLOAD *(q + 1) / (2 * NMI) - NLOAD * q / (2 * NMI)>([&](auto ic) {
+                    load_one(std::integral_constant<int, NLOAD * q / (2 * NMI) + decltype(ic)::value>{});
+                });
+        });
+    };
+    const int groups = p.nk / G;                        // (the host makes nk a multiple of 4)
+    for (int g = 0; g < groups; ++g) {
+        static_for<G / 2>([&](auto tc) {
+            constexpr int t = decltype(tc)::value;
+            half_iteration(g, std::integral_constant<int, 2 * t>{}, w0, w1);
+            half_iteration(g, std::integral_constant<int, 2 * t + 1>{}, w1, w0);
+        });
+    }
+    __builtin_amdgcn_s_waitcnt(WAIT_LOADS);             // the loads requested for groups beyond the last one have landed
 
     // ---- encoding recovery (Sec. 3.2): Y = accmul acc + mulA RA[row] + mulB RB[column] + c0, in wrapping 32-bit
     // arithmetic (the result fits int32, the host checks K (2^p - 1)(2^q - 1) < 2^31).

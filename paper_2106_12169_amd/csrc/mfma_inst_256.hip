@@ -20,16 +20,18 @@ bool launch_mfma256(const MfmaParams &p, int kindA, int kindB, bool conv, unsign
     }
 }
 
-bool launch_mfma_i8_c2(const MfmaParams &p, int classB, unsigned grid, hipStream_t st);
-bool launch_mfma_i8_c4(const MfmaParams &p, int classB, unsigned grid, hipStream_t st);
-bool launch_mfma_i8_c8(const MfmaParams &p, int classB, unsigned grid, hipStream_t st);
+bool launch_mfma_i8_c2(const MfmaParams &p, int classB, int group, unsigned grid, hipStream_t st);
+bool launch_mfma_i8_c4(const MfmaParams &p, int classB, int group, unsigned grid, hipStream_t st);
+bool launch_mfma_i8_c8(const MfmaParams &p, int classB, int group, unsigned grid, hipStream_t st);
 
 bool launch_mfma_i8(const MfmaParams &p, int classA, int classB, unsigned grid, hipStream_t st)
 {
+    // chunks fetched together: four (64 bytes of every plane row) while two group buffers fit the LDS, else two
+    const int group = (p.PA + p.PB) <= 9 ? 4 : 2;
     switch (classA) {
-        case 0: return launch_mfma_i8_c2(p, classB, grid, st);
-        case 1: return launch_mfma_i8_c4(p, classB, grid, st);
-        case 2: return launch_mfma_i8_c8(p, classB, grid, st);
+        case 0: return launch_mfma_i8_c2(p, classB, group, grid, st);
+        case 1: return launch_mfma_i8_c4(p, classB, group, grid, st);
+        case 2: return launch_mfma_i8_c8(p, classB, group, grid, st);
         default: return false;
     }
 }

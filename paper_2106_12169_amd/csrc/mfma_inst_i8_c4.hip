@@ -4,17 +4,29 @@
 
 namespace apnn {
 
-template <int CB> static void go(const MfmaParams &p, unsigned grid, hipStream_t st)
+template <int CB, int G> static bool go(const MfmaParams &p, unsigned grid, hipStream_t st)
 {
-    hipLaunchKernelGGL((mfma_i8_kernel<1, CB, 2, 2>), dim3(grid), dim3(256), 0, st, p);
+    auto kernel = mfma_i8_kernel<1, CB, 2, 2, G>;
+    const int lds = mfma_i8_lds_bytes(p.PA, p.PB, G);
+    static int granted = 0;                              // most dynamic LDS asked for so far (per instance)
+    if (lds > granted) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
+            return false;
+        granted = lds;
+    }
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(256), lds, st, p);
+    return true;
 }
 
-bool launch_mfma_i8_c4(const MfmaParams &p, int classB, unsigned grid, hipStream_t st)
+bool launch_mfma_i8_c4(const MfmaParams &p, int classB, int group, unsigned grid, hipStream_t st)
 {
-    switch (classB) {
-        case I8_C2: go<I8_C2>(p, grid, st); return true;
-        case I8_C4: go<I8_C4>(p, grid, st); return true;
-        case I8_C8: go<I8_C8>(p, grid, st); return true;
+    switch (classB * 8 + group) {
+        case I8_C2 * 8 + 4: return go<I8_C2, 4>(p, grid, st);
+        case I8_C4 * 8 + 4: return go<I8_C4, 4>(p, grid, st);
+        case I8_C8 * 8 + 4: return go<I8_C8, 4>(p, grid, st);
+        case I8_C2 * 8 + 2: return go<I8_C2, 2>(p, grid, st);
+        case I8_C4 * 8 + 2: return go<I8_C4, 2>(p, grid, st);
+        case I8_C8 * 8 + 2: return go<I8_C8, 2>(p, grid, st);
         default: return false;
     }
 }
