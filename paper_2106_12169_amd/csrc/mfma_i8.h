@@ -132,27 +132,44 @@ __device__ __forceinline__ void planes_to_bytes(const uint32_t (&w)[I8Slots<C>::
     }
 }
 
-// Bytes of LDS the kernel needs for PA + PB planes (two group buffers).
-constexpr int mfma_i8_lds_bytes(int PA, int PB, int G) { return 2 * (PA + PB) * 128 * G * 16; }
+// Bytes of LDS the kernel needs for PA + PB planes: two group buffers; with K split over wave pairs, room for the
+// exchange of half of every wave's accumulators (35 registers of 64 lanes for each of 8 waves).
+constexpr int mfma_i8_lds_bytes(int PA, int PB, int G, int NKS)
+{
+    const int tiles = 2 * (PA + PB) * 128 * G * 16, exchange = NKS == 2 ? 8 * 35 * 256 : 0;
+    return tiles > exchange ? tiles : exchange;
+}
 
-template <int CA, int CB, int FM, int FN, int G>
-__global__ __launch_bounds__(256, 1) void mfma_i8_kernel(const MfmaParams p)
+// NKS = 2: eight waves, two per SIMD; the two waves of a pair own the same 64 x 64 outputs and take alternate
+// chunks of K, and add their halves through LDS at the end.  A lone wave issues a vector instruction only every
+// six cycles or so (measured; two waves together reach one per four), and this kernel is bound by them.
+template <int CA, int CB, int FM, int FN, int G, int NKS>
+__global__ __launch_bounds__(256 * NKS, 1) void mfma_i8_kernel(const MfmaParams p)
 {
     static_assert(G == 2 || G == 4, "a group is two or four chunks");
+    static_assert(NKS == 1 || NKS == 2, "K is split over at most two waves");
     static_assert(FM == 2 && FN == 2, "128 x 128 block tile");
     constexpr int SA = I8Slots<CA>::value, SB = I8Slots<CB>::value;     // most planes of the class: width of the transposition
     constexpr int BM = 2 * FM * 32, BN = 2 * FN * 32;
+    constexpr int NW = 4 * NKS;                         // waves
     constexpr int RB = 64 / G;                          // rows one load instruction covers (G pieces each)
-    constexpr int KK = BM / RB / 4;                     // load instructions per plane, operand and wave
+    constexpr int NBR = BM / RB;                        // row blocks (load instructions) per plane
+    constexpr int CPW = G / NKS;                        // chunks of a group that one wave multiplies
     // A group buffer holds, for G chunks: A planes [PA][BM rows][G pieces of 16 bytes], then B planes [PB][BN][G].
     extern __shared__ __attribute__((aligned(1024))) uint32_t smem[];
     typedef __attribute__((address_space(3))) uint32_t *lds_ptr_t;
     const uint32_t smem_base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_ptr_t)smem));
     const int a_bytes = p.PA * BM * G * 16, buf_bytes = a_bytes + p.PB * BN * G * 16;
+    // Plane counts for the "does this plane exist" tests around loads and reads.  Kept opaque (see fresh_counts) so
+    // that every test is a scalar compare where it stands; hoisted out of the loop, the two dozen tests lived as lane
+    // masks in scalar register pairs, which spilled.
+    int n_pa = p.PA, n_pb = p.PB;
+    auto fresh_counts = [&]() __attribute__((always_inline)) { asm volatile("" : "+s"(n_pa), "+s"(n_pb)); };
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave >> 1, wn = wave & 1;
+    const int pair = wave & 3, ks = wave >> 2;          // position in the 2 x 2 arrangement of wave tiles, K share
+    const int wm = pair >> 1, wn = pair & 1;
     const int lr = lane & 31, lh = lane >> 5;
 
     const int tilesN = (p.N + BN - 1) / BN;
@@ -174,6 +191,7 @@ __global__ __launch_bounds__(256, 1) void mfma_i8_kernel(const MfmaParams p)
     // slot j ^ swz(r') of the row, so that the reads of 8 consecutive rows spread over all banks.  The per-lane part
     // of the byte offset is the same for every instruction; the rest (plane, row block, group) is wave-uniform and
     // added on, and the whole sum is what the hardware checks against the operand's size: rows beyond M read zeros.
+    // The (plane, row block) pairs of an operand are dealt to the waves in turn.
     auto swz = [](int r) { return G == 4 ? ((r >> 1) & 3) : ((r >> 2) & 1); };
     const uint32_t bytesA = 4u * static_cast<uint32_t>(p.M) * p.PA * p.ldwA, bytesB = 4u * static_cast<uint32_t>(p.N) * p.PB * p.ldwB;
     const v4u_t descA = make_raw_desc(p.A, bytesA), descB = make_raw_desc(p.B, bytesB);
@@ -185,61 +203,68 @@ __global__ __launch_bounds__(256, 1) void mfma_i8_kernel(const MfmaParams p)
     uint32_t gl_offA = 0, gl_offB = 0;
     uint32_t gl_lds = 0;
     int gl_k = 0;
-    auto begin_group = [&](int group, uint32_t lds_bytes_base) {
+    auto begin_group = [&](int group, uint32_t lds_bytes_base) __attribute__((always_inline)) {
         const uint32_t dead = 4 * (group * G + ld_piece) < p.Kw ? 0u : OUT_OF_RANGE;
         gl_offA = lane_offA | dead;
         gl_offB = lane_offB | dead;
         gl_lds = lds_bytes_base;
         gl_k = __builtin_amdgcn_readfirstlane(group * G * 16);
     };
-    // load instruction d of the group, 0 <= d < (SA + SB) KK: plane d / KK of A, then of B; skipped for planes that do not exist
-    auto load_one = [&](auto dc) {
+    // load instruction d of this wave for the group: (plane, row block) number wave + NW d of A, then of B;
+    // skipped for planes that do not exist
+    constexpr int NDA = (SA * NBR + NW - 1) / NW, NDB = (SB * NBR + NW - 1) / NW, NLOAD = NDA + NDB;
+    auto uniform_desc = [](v4u_t d) __attribute__((always_inline)) {     // (wave-uniform by construction; saying so at the point of use
+        v4u_t r;                                        // keeps the four words in scalar registers for the instruction)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) r[i] = __builtin_amdgcn_readfirstlane(d[i]);
+        return r;
+    };
+    auto load_one = [&](auto dc) __attribute__((always_inline)) {
         constexpr int d = decltype(dc)::value;
-        if constexpr (d < SA * KK) {
-            constexpr int s = d / KK, kk = d % KK;
-            if (s < p.PA) {
-                const int b = wave + 4 * kk;            // row block
+        if constexpr (d < NDA) {
+            const int n = wave + NW * d, s = n / NBR, b = n % NBR;
+            if (s < n_pa) {
                 const uint32_t uni = 4u * static_cast<uint32_t>(b * RB * p.PA + s) * p.ldwA + gl_k;
-                load_to_lds_16(descA, __builtin_amdgcn_readfirstlane(gl_lds + (s * (BM / RB) + b) * 1024), gl_offA + uni, 0);
+                load_to_lds_16(uniform_desc(descA), __builtin_amdgcn_readfirstlane(gl_lds + n * 1024), gl_offA + uni, 0);
             }
         } else {
-            constexpr int s = (d - SA * KK) / KK, kk = (d - SA * KK) % KK;
-            if (s < p.PB) {
-                const int b = wave + 4 * kk;
+            const int n = wave + NW * (d - NDA), s = n / NBR, b = n % NBR;
+            if (s < n_pb) {
                 const uint32_t uni = 4u * static_cast<uint32_t>(b * RB * p.PB + s) * p.ldwB + gl_k;
-                load_to_lds_16(descB, __builtin_amdgcn_readfirstlane(gl_lds + a_bytes + (s * (BN / RB) + b) * 1024), gl_offB + uni, 0);
+                load_to_lds_16(uniform_desc(descB), __builtin_amdgcn_readfirstlane(gl_lds + a_bytes + n * 1024), gl_offB + uni, 0);
             }
         }
     };
-    constexpr int NLOAD = (SA + SB) * KK;
     constexpr int WAIT_LOADS = 0x0F70;                  // s_waitcnt vmcnt(0) (expcnt, lgkmcnt untouched)
 
     // ---- reader.  Lane (half h, row r) reads words 2h, 2h + 1 of chunk j of plane s of fragment row f at byte
     //   buffer + ((s BM + tile row) G + (j ^ swz(r))) 16 + 8 h;
-    // the per-lane part (one register per j, rebuilt when the buffer changes) plus a constant that fits the
-    // instruction's offset field.
-    uint32_t rd0A[G], rd0B[G], rdA[G], rdB[G];
+    // the per-lane part (one register for each of this wave's chunks of a group, rebuilt when the buffer changes)
+    // plus a constant that fits the instruction's offset field.  This wave's chunks of a group: ks, ks + NKS, ...
+    uint32_t rd0A[CPW], rd0B[CPW], rdA[CPW], rdB[CPW];
 #pragma unroll
-    for (int j = 0; j < G; ++j) {
-        rd0A[j] = ((wm * FM * 32 + lr) * G + (j ^ swz(lr & (RB - 1)))) * 16 + 8 * lh;
-        rd0B[j] = a_bytes + ((wn * FN * 32 + lr) * G + (j ^ swz(lr & (RB - 1)))) * 16 + 8 * lh;
+    for (int t = 0; t < CPW; ++t) {
+        const int j = t * NKS + ks;
+        rd0A[t] = ((wm * FM * 32 + lr) * G + (j ^ swz(lr & (RB - 1)))) * 16 + 8 * lh;
+        rd0B[t] = a_bytes + ((wn * FN * 32 + lr) * G + (j ^ swz(lr & (RB - 1)))) * 16 + 8 * lh;
     }
-    auto set_read_buffer = [&](uint32_t byte_base) {
+    auto set_read_buffer = [&](uint32_t byte_base) __attribute__((always_inline)) {
 #pragma unroll
-        for (int j = 0; j < G; ++j) { rdA[j] = rd0A[j] + byte_base; rdB[j] = rd0B[j] + byte_base; }
+        for (int t = 0; t < CPW; ++t) { rdA[t] = rd0A[t] + byte_base; rdB[t] = rd0B[t] + byte_base; }
     };
     struct Words { uint2 a[FM][SA], b[FN][SB]; };       // this lane's two words of every plane of its fragment rows
     constexpr int NREAD = FM * SA + FN * SB;
-    // read r of chunk j: (fragment, plane) of A, then of B; words of planes that do not exist stay zero
-    auto read_one = [&](auto jc, auto rc, Words &w) {
-        constexpr int j = decltype(jc)::value, r = decltype(rc)::value;
+    // read r of this wave's chunk t of the group: (fragment, plane) of A, then of B; words of planes that do not
+    // exist stay zero
+    auto read_one = [&](auto tc, auto rc, Words &w) __attribute__((always_inline)) {
+        constexpr int t = decltype(tc)::value, r = decltype(rc)::value;
         const char *lds = reinterpret_cast<const char *>(smem);
         if constexpr (r < FM * SA) {
             constexpr int f = r / SA, s = r % SA;
-            if (s < p.PA) w.a[f][s] = *reinterpret_cast<const uint2 *>(lds + rdA[j] + (s * BM + 32 * f) * G * 16);
+            if (s < n_pa) w.a[f][s] = *reinterpret_cast<const uint2 *>(lds + rdA[t] + (s * BM + 32 * f) * G * 16);
         } else {
             constexpr int f = (r - FM * SA) / SB, s = (r - FM * SA) % SB;
-            if (s < p.PB) w.b[f][s] = *reinterpret_cast<const uint2 *>(lds + rdB[j] + (s * BN + 32 * f) * G * 16);
+            if (s < n_pb) w.b[f][s] = *reinterpret_cast<const uint2 *>(lds + rdB[t] + (s * BN + 32 * f) * G * 16);
         }
     };
 
@@ -256,7 +281,7 @@ __global__ __launch_bounds__(256, 1) void mfma_i8_kernel(const MfmaParams p)
 #pragma unroll
     for (int j = 0; j < FN; ++j) rb[j] = 0;
     const bool need_ra = p.mulA != 0, need_rb = p.mulB != 0;
-    auto row_sums = [&](const Words &w) {               // (before the top plane of an 8-bit operand is inverted)
+    auto row_sums = [&](const Words &w) __attribute__((always_inline)) {      // (before the top plane of an 8-bit operand is inverted)
         if (need_ra) {
 #pragma unroll
             for (int f = 0; f < FM; ++f)
@@ -274,13 +299,13 @@ __global__ __launch_bounds__(256, 1) void mfma_i8_kernel(const MfmaParams p)
 
     // One phase: the 2 FM FN matrix instructions of one word (bytes `cur`), each followed by its share of the
     // transposition of word E of `wsrc` into `nxt` (cut into 2 (FM + FN) pieces) and by whatever memory
-    // instructions `hook` deals to that slot.  A lone wave issues in order: loads and LDS reads issued in a burst
+    // instructions `hook` deals to that slot.  A wave issues in order: loads and LDS reads issued in a burst
     // held up the vector instructions behind them, spread out like this they run underneath.
     constexpr int NMI = 2 * FM * FN, NPART = 2 * (FM + FN);
-    auto phase = [&](const Bytes &cur, const Words &wsrc, auto enc, Bytes &nxt, auto &&hook) {
+    auto phase = [&](const Bytes &cur, const Words &wsrc, auto enc, Bytes &nxt, auto &&hook) __attribute__((always_inline)) {
         constexpr int E = decltype(enc)::value;
         uint32_t x[8];
-        auto part = [&](auto pc) {
+        auto part = [&](auto pc) __attribute__((always_inline)) {
             constexpr int pi = decltype(pc)::value, f = pi / 2, half = pi % 2;
             if constexpr (f < FM) {
                 uint32_t w[SA];
@@ -314,11 +339,11 @@ __global__ __launch_bounds__(256, 1) void mfma_i8_kernel(const MfmaParams p)
     using E0 = std::integral_constant<int, 0>;
     using E1 = std::integral_constant<int, 1>;
 
-    // Group g (chunks G g .. G g + G - 1) lives in buffer g mod 2.  The half-iteration of chunk c multiplies chunk c
-    // while it reads the words of chunk c + 1 and transposes the second word of chunk c and the first of chunk c + 1.
-    // In the last half-iteration of group g: group g + 1 has landed (wait, barrier -- the only ones of the group), the
-    // reads move over to its buffer, and group g + 2 is requested into the buffer of group g, whose words every wave
-    // has in registers by then; it is needed a whole group later.  Chunks beyond the last are zeros that nobody multiplies.
+    // Group g (chunks G g .. G g + G - 1) lives in buffer g mod 2.  A wave's half-iteration multiplies one of its
+    // chunks while it reads the words of its next chunk and transposes the second word of the one and the first of
+    // the other.  In its last half-iteration of group g: group g + 1 has landed (wait, barrier -- the only ones of the
+    // group), the reads move over to its buffer, and group g + 2 is requested into the buffer of group g, whose words
+    // every wave has in registers by then; it is needed a whole group later.  Chunks beyond the last are zeros.
     Words w0, w1;
     Bytes by0, by1;
 #pragma unroll
@@ -352,98 +377,142 @@ __global__ __launch_bounds__(256, 1) void mfma_i8_kernel(const MfmaParams p)
         row_sums(w0);
         phase(dummy, w0, E0{}, by0, no_hook);
     }
-    auto half_iteration = [&](int group, auto jjc, Words &wc, Words &wn_) {
-        constexpr int jj = decltype(jjc)::value, jn = (jj + 1) % G;     // chunk of the group being multiplied / read
-        constexpr bool LAST = jj == G - 1;
+    int group = 0;                                      // group of the chunk being multiplied
+    auto half_iteration = [&](auto tc, Words &wc, Words &wn_) __attribute__((always_inline)) {
+        constexpr int t = decltype(tc)::value, tn = (t + 1) % CPW;     // this wave's chunk of the group being multiplied / read
+        constexpr bool LAST = t == CPW - 1;
+        fresh_counts();
         if constexpr (LAST) {
             __builtin_amdgcn_s_waitcnt(WAIT_LOADS);     // this wave's share of group + 1 is in LDS
             __syncthreads();
             begin_group(group + 2, smem_base + cur_base);
             cur_base = cur_base ? 0u : static_cast<uint32_t>(buf_bytes);
             set_read_buffer(cur_base);
+            ++group;
         }
-        // first phase: the reads of chunk c + 1, and the first half of the group's loads
+        // first phase: the reads of the next chunk, and this wave's loads of the group (as early as the buffer is free)
         phase(by0, wc, E1{}, by1, [&](auto qc) {
             constexpr int q = decltype(qc)::value;
             static_for<NREAD *(q + 1) / NMI - NREAD * q / NMI>([&](auto ic) {
-                read_one(std::integral_constant<int, jn>{}, std::integral_constant<int, NREAD * q / NMI + decltype(ic)::value>{}, wn_);
+                read_one(std::integral_constant<int, tn>{}, std::integral_constant<int, NREAD * q / NMI + decltype(ic)::value>{}, wn_);
             });
             if constexpr (LAST)
-                static_for<NLOAD *(q + 1) / (2 * NMI) - NLOAD * q / (2 * NMI)>([&](auto ic) {
-                    load_one(std::integral_constant<int, NLOAD * q / (2 * NMI) + decltype(ic)::value>{});
+                static_for<NLOAD *(q + 1) / NMI - NLOAD * q / NMI>([&](auto ic) {
+                    load_one(std::integral_constant<int, NLOAD * q / NMI + decltype(ic)::value>{});
                 });
         });
         row_sums(wn_);
-        phase(by1, wn_, E0{}, by0, [&](auto qc) {
-            constexpr int q = decltype(qc)::value + NMI;
-            if constexpr (LAST)
-                static_for<NLOAD *(q + 1) / (2 * NMI) - NLOAD * q / (2 * NMI)>([&](auto ic) {
-                    load_one(std::integral_constant<int, NLOAD * q / (2 * NMI) + decltype(ic)::value>{});
-                });
-        });
+        phase(by1, wn_, E0{}, by0, no_hook);
     };
-    const int groups = p.nk / G;                        // (the host makes nk a multiple of 4)
-    for (int g = 0; g < groups; ++g) {
-        static_for<G / 2>([&](auto tc) {
-            constexpr int t = decltype(tc)::value;
-            half_iteration(g, std::integral_constant<int, 2 * t>{}, w0, w1);
-            half_iteration(g, std::integral_constant<int, 2 * t + 1>{}, w1, w0);
+    // (the host makes nk a multiple of 4: whole groups, and an even number of chunks for every wave)
+    constexpr int UNROLL = CPW % 2 == 0 ? CPW : 2 * CPW;
+    for (int u = 0; u < p.nk / NKS; u += UNROLL) {
+        static_for<UNROLL / 2>([&](auto vc) {
+            constexpr int v = decltype(vc)::value;
+            half_iteration(std::integral_constant<int, (2 * v) % CPW>{}, w0, w1);
+            half_iteration(std::integral_constant<int, (2 * v + 1) % CPW>{}, w1, w0);
         });
     }
     __builtin_amdgcn_s_waitcnt(WAIT_LOADS);             // the loads requested for groups beyond the last one have landed
 
-    // ---- encoding recovery (Sec. 3.2): Y = accmul acc + mulA RA[row] + mulB RB[column] + c0, in wrapping 32-bit
-    // arithmetic (the result fits int32, the host checks K (2^p - 1)(2^q - 1) < 2^31).
-    // The two lane halves hold the sums of different words of the same row.
+    // The two lane halves hold the row sums of different words of the same row.
 #pragma unroll
-    for (int i = 0; i < FM; ++i) ra[i] = (ra[i] + static_cast<uint32_t>(__shfl_xor(static_cast<int>(ra[i]), 32))) * static_cast<uint32_t>(p.mulA);
+    for (int i = 0; i < FM; ++i) ra[i] += static_cast<uint32_t>(__shfl_xor(static_cast<int>(ra[i]), 32));
 #pragma unroll
-    for (int j = 0; j < FN; ++j)
-        rb[j] = (rb[j] + static_cast<uint32_t>(__shfl_xor(static_cast<int>(rb[j]), 32))) * static_cast<uint32_t>(p.mulB) + static_cast<uint32_t>(p.c0);
-    // accumulator register r of lane (lh, lr) is row 8 (r / 4) + 4 lh + r % 4, column lr
-    static_for<FM>([&](auto ic) {
-        constexpr int i = decltype(ic)::value;
+    for (int j = 0; j < FN; ++j) rb[j] += static_cast<uint32_t>(__shfl_xor(static_cast<int>(rb[j]), 32));
+
+    // ---- one row of wave tiles (32 rows x FN tiles): encoding recovery (Sec. 3.2) and the outputs.
+    //   Y = accmul acc + mulA RA[row] + mulB RB[column] + c0, in wrapping 32-bit arithmetic (the result fits int32,
+    // the host checks K (2^p - 1)(2^q - 1) < 2^31).
+    auto finish_tile_row = [&](int irow, v16i_t (&t)[FN], uint32_t ra_row) __attribute__((always_inline)) {
+        const uint32_t ra_m = ra_row * static_cast<uint32_t>(p.mulA);
+        uint32_t col[FN];
+#pragma unroll
+        for (int j = 0; j < FN; ++j) col[j] = rb[j] * static_cast<uint32_t>(p.mulB) + static_cast<uint32_t>(p.c0);
+        // accumulator register r of lane (lh, lr) is row 8 (r / 4) + 4 lh + r % 4, column lr
         static_for<16>([&](auto rc) {
             constexpr int r = decltype(rc)::value;
             const int row = 8 * (r >> 2) + 4 * lh + (r & 3);
-            const uint32_t rowterm = need_ra ? static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(4 * row, static_cast<int>(ra[i]))) : 0u;
-            static_for<FN>([&](auto jc) {
-                constexpr int j = decltype(jc)::value;
-                acc[i][j][r] = static_cast<int>(static_cast<uint32_t>(acc[i][j][r]) * static_cast<uint32_t>(p.accmul) + rowterm + rb[j]);
+            const uint32_t rowterm = need_ra ? static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(4 * row, static_cast<int>(ra_m))) : 0u;
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+                t[j][r] = static_cast<int>(static_cast<uint32_t>(t[j][r]) * static_cast<uint32_t>(p.accmul) + rowterm + col[j]);
+        });
+        const int mrow0 = m0 + wm * FM * 32 + irow * 32;            // first row of this row of wave tiles
+        if (p.Y) {
+            // int32 output straight from the accumulators: one store instruction writes two 128-byte row segments.
+            // The whole byte offset travels in the per-lane offset, which the hardware checks against M x N.
+            const __amdgpu_buffer_rsrc_t rsrcY =
+                __builtin_amdgcn_make_buffer_rsrc(p.Y, 0, 4u * static_cast<uint32_t>(p.M) * p.N, 0x00020000);
+            const int gn0 = n0 + wn * FN * 32 + lr;
+            const uint32_t vbase = 4u * (static_cast<uint32_t>(mrow0 + 4 * lh) * p.N + gn0);
+            static_for<FN * 16>([&](auto c) {
+                constexpr int j = decltype(c)::value / 16, r = decltype(c)::value % 16;
+                constexpr int row = 8 * (r >> 2) + (r & 3);
+                const uint32_t voff = (vbase + 128u * j) | (gn0 + 32 * j < p.N ? 0u : OUT_OF_RANGE);
+                __builtin_amdgcn_raw_buffer_store_b32(t[j][r], rsrcY, voff + 4u * row * static_cast<uint32_t>(p.N), 0, 0);
+            });
+        }
+        if (!p.scale) return;
+        MfmaParams pe = p;                              // the shared epilogue sees finished integers
+        pe.out_scale = 1.0f; pe.c0 = 0; pe.Y = nullptr;
+        static_for<FN>([&](auto jc) {
+            constexpr int j = decltype(jc)::value;
+            const int gn = n0 + wn * FN * 32 + j * 32 + lr;
+            float sc = 0.0f, bi = 0.0f;
+            if (gn < p.N) { sc = p.scale[gn]; bi = p.bias[gn]; }
+            static_for<4>([&](auto kc) {
+                constexpr int k = decltype(kc)::value;
+                const int row0 = mrow0 + 8 * k;
+                const float v4[4] = {static_cast<float>(t[j][4 * k]), static_cast<float>(t[j][4 * k + 1]),
+                                     static_cast<float>(t[j][4 * k + 2]), static_cast<float>(t[j][4 * k + 3])};
+                finish_rows8(pe, v4, row0, gn, sc, bi, load_res_rows8(pe, row0, gn >> 5, lane), lane, lr, lh);
             });
         });
-    });
+    };
 
-    if (p.Y) {
-        // int32 output straight from the accumulators: one store instruction writes two 128-byte row segments.
-        // The whole byte offset travels in the per-lane offset, which the hardware checks against M x N.
-        const __amdgpu_buffer_rsrc_t rsrcY =
-            __builtin_amdgcn_make_buffer_rsrc(p.Y, 0, 4u * static_cast<uint32_t>(p.M) * p.N, 0x00020000);
-        const int gn0 = n0 + wn * FN * 32 + lr;
-        const uint32_t vbase = 4u * (static_cast<uint32_t>(m0 + wm * FM * 32 + 4 * lh) * p.N + gn0);
-        static_for<FM * FN * 16>([&](auto c) {
-            constexpr int i = decltype(c)::value / (FN * 16), j = decltype(c)::value / 16 % FN, r = decltype(c)::value % 16;
-            constexpr int row = i * 32 + 8 * (r >> 2) + (r & 3);
-            const uint32_t voff = (vbase + 128u * j) | (gn0 + 32 * j < p.N ? 0u : OUT_OF_RANGE);
-            __builtin_amdgcn_raw_buffer_store_b32(acc[i][j][r], rsrcY, voff + 4u * row * static_cast<uint32_t>(p.N), 0, 0);
-        });
+    if constexpr (NKS == 1) {
+        static_for<FM>([&](auto ic) { finish_tile_row(decltype(ic)::value, acc[decltype(ic)::value], ra[decltype(ic)::value]); });
+    } else {
+        // The waves of a pair add their halves: wave ks keeps tile row ks, hands the other one (and its row sums) to
+        // its partner through LDS, and finishes its own.  Per wave: FN 16 accumulator registers, one row-sum register
+        // of A, FN of B, of 64 lanes each.
+        constexpr int XREGS = FN * 16 + 1 + FN;
+        __syncthreads();                                // every wave is done with the operand tiles
+        uint32_t *xch = smem + (wave * XREGS) * 64 + lane, *from = smem + ((wave ^ 4) * XREGS) * 64 + lane;
+        v16i_t mine[FN];
+        uint32_t ra_mine;
+        if (ks == 0) {
+#pragma unroll
+            for (int j = 0; j < FN; ++j) {
+                mine[j] = acc[0][j];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) xch[(j * 16 + r) * 64] = static_cast<uint32_t>(acc[1][j][r]);
+            }
+            ra_mine = ra[0];
+            xch[FN * 16 * 64] = ra[1];
+        } else {
+#pragma unroll
+            for (int j = 0; j < FN; ++j) {
+                mine[j] = acc[1][j];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) xch[(j * 16 + r) * 64] = static_cast<uint32_t>(acc[0][j][r]);
+            }
+            ra_mine = ra[1];
+            xch[FN * 16 * 64] = ra[0];
+        }
+#pragma unroll
+        for (int j = 0; j < FN; ++j) xch[(FN * 16 + 1 + j) * 64] = rb[j];
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) mine[j][r] += static_cast<int>(from[(j * 16 + r) * 64]);
+            rb[j] += from[(FN * 16 + 1 + j) * 64];
+        }
+        ra_mine += from[FN * 16 * 64];
+        finish_tile_row(ks, mine, ra_mine);
     }
-    if (!p.scale) return;
-    MfmaParams pe = p;                                  // the shared epilogue sees finished integers
-    pe.out_scale = 1.0f; pe.c0 = 0; pe.Y = nullptr;
-    static_for<FN>([&](auto jc) {
-        constexpr int j = decltype(jc)::value;
-        const int gn = n0 + wn * FN * 32 + j * 32 + lr;
-        float sc = 0.0f, bi = 0.0f;
-        if (gn < p.N) { sc = p.scale[gn]; bi = p.bias[gn]; }
-        static_for<FM * 4>([&](auto ikc) {
-            constexpr int i = decltype(ikc)::value / 4, k = decltype(ikc)::value % 4;
-            const int row0 = m0 + wm * FM * 32 + i * 32 + 8 * k;
-            const float v4[4] = {static_cast<float>(acc[i][j][4 * k]), static_cast<float>(acc[i][j][4 * k + 1]),
-                                 static_cast<float>(acc[i][j][4 * k + 2]), static_cast<float>(acc[i][j][4 * k + 3])};
-            finish_rows8(pe, v4, row0, gn, sc, bi, load_res_rows8(pe, row0, gn >> 5, lane), lane, lr, lh);
-        });
-    });
 }
 
 }  // namespace apnn

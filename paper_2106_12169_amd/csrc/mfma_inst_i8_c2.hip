@@ -4,17 +4,20 @@
 
 namespace apnn {
 
+// Two waves per SIMD (K split over wave pairs) while the registers of a wave hold its plane words twice over;
+// the widest class pair runs one wave per SIMD.
 template <int CB, int G> static bool go(const MfmaParams &p, unsigned grid, hipStream_t st)
 {
-    auto kernel = mfma_i8_kernel<0, CB, 2, 2, G>;
-    const int lds = mfma_i8_lds_bytes(p.PA, p.PB, G);
+    constexpr int NKS = I8Slots<0>::value + I8Slots<CB>::value <= 12 ? 2 : 1;
+    auto kernel = mfma_i8_kernel<0, CB, 2, 2, G, NKS>;
+    const int lds = mfma_i8_lds_bytes(p.PA, p.PB, G, NKS);
     static int granted = 0;                              // most dynamic LDS asked for so far (per instance)
     if (lds > granted) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
             return false;
         granted = lds;
     }
-    hipLaunchKernelGGL(kernel, dim3(grid), dim3(256), lds, st, p);
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(256 * NKS), lds, st, p);
     return true;
 }
 
