@@ -454,6 +454,29 @@ def extra_configs(B, wl, dev, graph_time, with_cpu=True):
                                             "library_calls": net128.launches}
     del net128, img128
 
+    # AlexNet- and VGG-16-shaped chains (the paper's other two models, Sec. 6.2; layer shapes are this build's, the
+    # paper prints none), batch 8, w1a2 after the 8-bit input layer; oracle check on the first images of the batch.
+    for name, make, ncheck in (("alexnet_shaped_w1a2_batch8", wl.alexnet_layers, 8), ("vgg16_shaped_w1a2_batch8", wl.vgg16_layers, 2)):
+        ls = make()
+        ps = wl.network_params(ls)
+        netx = PackedNet(ls, ps, 8)
+        imgx_np = wl.image_batch(2006, 8, 224)
+        imgx = dev(imgx_np)
+        tx = graph_time(lambda: netx.forward(imgx), reps=1, replays=20)
+        mx = sum(8 * L.Ho * L.Wo * L.Cout * L.Cin * L.R * L.S for L in ls if L.kind in ("conv", "fc"))
+        ex[name] = {"ms": round(tx * 1e3, 4), "library_calls": netx.launches, "images_per_s": round(8 / tx),
+                    "eff_tops": round(2.0 * mx / tx / 1e12, 2), "matrix_frac_vs_fp4_peak": round(2.0 * mx / tx / MFMA_FP4_PEAK, 4)}
+        if with_cpu:
+            t0 = time.perf_counter()
+            wantx = onet.run(ls, ps, imgx_np[:ncheck])[ls[-1].name]
+            ex[name]["cpu_oracle_s"] = round(time.perf_counter() - t0, 3)
+            ex[name]["cpu_oracle_images"] = ncheck
+            lx = netx.forward(imgx)
+            torch.cuda.synchronize()
+            assert np.array_equal(lx.cpu().numpy()[:ncheck], wantx), f"{name}: logits differ from the oracle"
+            ex[name]["bit_exact_vs_oracle"] = True
+        del netx, imgx
+
     # The network's input layer (8-bit image x 1-bit weights, 7 x 7 stride 2) in its three forms: the 8-bit integer
     # matrix instruction straight from the image, and receptive-field planes multiplied by the FP4 matrix-core
     # kernel (4 digit passes) or by the AND+popcount kernel (8 plane passes).

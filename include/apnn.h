@@ -212,11 +212,11 @@ int apnn_layer_pair(const apnn_layer_desc *descA, const uint32_t *WA_dev, const 
  * integer results.
  *
  * apnn_pack_input_weights: src_dev holds Cout x Cin x R x S values, one per byte
- * (-1/+1 as int8, or unsigned codes below 2^bits, bits <= 7; S <= 8).  dst_dev
- * receives apnn_input_weight_bytes(Cout, Cin, R) bytes: signed-byte rows in the
+ * (-1/+1 as int8, or unsigned codes below 2^bits, bits <= 7; S <= 16).  dst_dev
+ * receives apnn_input_weight_bytes(Cout, Cin, R, S) bytes: signed-byte rows in the
  * kernel's K order, then one int32 per output channel (128 x the row sum, the
  * constant that lets the image enter as signed bytes x - 128). */
-size_t apnn_input_weight_bytes(int64_t Cout, int64_t Cin, int R);
+size_t apnn_input_weight_bytes(int64_t Cout, int64_t Cin, int R, int S);
 int apnn_pack_input_weights(const void *src_dev, int64_t Cout, int64_t Cin, int R, int S, int bits,
                             apnn_encoding enc, void *dst_dev, void *stream);
 
@@ -225,7 +225,7 @@ int apnn_pack_input_weights(const void *src_dev, int64_t Cout, int64_t Cin, int 
  * byte are ignored; conv.encX must be APNN_ENC_UNSIGNED), W_dev from apnn_pack_input_weights, then the epilogue and
  * the outputs of apnn_layer (acc_out_dev, float_out_dev, residual, q_out planes in
  * [pixel][q_out][Cout/32]).  desc->is_gemm and desc->pool must be 0.
- * APNN_ERR_UNSUPPORTED unless S <= 8, W >= 8, p <= 7, Cout <= 128 and
+ * APNN_ERR_UNSUPPORTED unless S <= 16, W >= 8, p <= 7, Cout <= 128 and
  * 255 K max|w| < 2^24. */
 int apnn_input_layer(const apnn_layer_desc *desc, const void *W_dev, const uint8_t *image_dev,
                      uint32_t *out_packed_dev, void *stream);

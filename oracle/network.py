@@ -16,7 +16,7 @@ from __future__ import annotations
 
 import numpy as np
 
-from . import conv2d, epilogue, gemm, maxpool, sumpool
+from . import POOL_MAX, conv2d, epilogue, gemm, gridpool, maxpool, sumpool
 
 ENC_UNSIGNED, ENC_PM1 = 0, 1
 
@@ -32,6 +32,8 @@ def run(layers, params, image_nchw):
         if L.kind == "conv":
             w, scale, bias = params[L.name]
             acc = conv2d(w, ENC_PM1, L.p, x, ENC_UNSIGNED, L.q, L.stride, L.pad)
+            if getattr(L, "pool", 0):                   # 2 x 2 max pooling of the integer results, then the epilogue (Sec. 5.2)
+                acc = gridpool(acc, 2, POOL_MAX)
             res = out[L.res] if L.res else None
             codes, _ = epilogue(acc, scale, bias, L.q_out, res=res, res_scale=L.res_scale)
             out[L.name] = codes

@@ -82,7 +82,7 @@ def lib():
     L.apnn_layer.argtypes = [C.POINTER(LayerDesc), vp, vp, vp, vp]
     L.apnn_layer_pair.argtypes = [C.POINTER(LayerDesc), vp, vp, vp, C.POINTER(LayerDesc), vp, vp, vp, vp]
     L.apnn_input_weight_bytes.restype = C.c_size_t
-    L.apnn_input_weight_bytes.argtypes = [i64, i64, i32]
+    L.apnn_input_weight_bytes.argtypes = [i64, i64, i32, i32]
     L.apnn_pack_input_weights.argtypes = [vp, i64, i64, i32, i32, i32, i32, vp, vp]
     L.apnn_input_layer.argtypes = [C.POINTER(LayerDesc), vp, vp, vp, vp]
     L.apnn_fold_bn.argtypes = [vp, vp, vp, vp, C.c_double, C.c_double, C.c_double, i64, vp, vp]
@@ -269,7 +269,7 @@ def apnn_layer_pair(a: dict, b: dict) -> None:
 def apnn_pack_input_weights(src: torch.Tensor, bits: int, enc: int) -> torch.Tensor:
     """src: Cout x Cin x R x S values, one per byte -> the input layer's signed-byte weight rows."""
     Cout, Cin, R, S = src.shape
-    out = torch.empty(max(lib().apnn_input_weight_bytes(Cout, Cin, R), 16), dtype=torch.uint8, device=src.device)
+    out = torch.empty(max(lib().apnn_input_weight_bytes(Cout, Cin, R, S), 16), dtype=torch.uint8, device=src.device)
     _check(lib().apnn_pack_input_weights(_ptr(src), Cout, Cin, R, S, bits, enc, _ptr(out), _stream()))
     return out
 

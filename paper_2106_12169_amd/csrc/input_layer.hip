@@ -10,9 +10,10 @@
 // are the same integers.
 //
 // Implicit GEMM straight from the N x C x H x W image: row = output pixel,
-// column = output channel, K position (c, r, s) at byte (c R + r) * 8 + s of a K
-// row (S <= 8; bytes s >= S carry weight 0).  One K segment of a pixel is thus 8
-// consecutive image bytes, one unaligned 8-byte load per lane.  The matrix
+// column = output channel, K position (c, r, s) at byte ((c R + r) SEG + s / 8) * 8
+// + s % 8 of a K row, SEG = 1 for S <= 8 and 2 for S <= 16 (bytes s >= S carry
+// weight 0).  One K segment of a pixel is thus 8 consecutive image bytes, one
+// unaligned 8-byte load per lane.  The matrix
 // instruction multiplies signed bytes: image bytes enter as x - 128 (one XOR) and
 // the per-channel constant 128 * sum_k w[k], made by the weight packer, is added
 // back in the epilogue; positions outside the frame are x = 0, i.e. -128, and are
@@ -29,14 +30,16 @@ struct InputParams {
     const uint8_t *img;     // N x C x H x W bytes
     const int8_t *w;        // Cout x Kp signed bytes
     const int32_t *cterm;   // Cout: 128 * sum of the row's weights
-    int C, Kp, KS, nseg;    // channels, bytes per weight row, steps of 32 bytes, K segments C * R
+    int C, Kp, KS, nseg;    // channels, bytes per weight row, steps of 32 bytes, K segments C * R * SEG
     float invR;
     uint32_t xmask;         // (2^q - 1) in every byte: image bits above the q significant ones are ignored
 };
 
 // One wave per 32-pixel row tile, all NT column tiles of 32 channels; steps of 32 K bytes:
 // lane (half lh, row lr) supplies K bytes 16 lh .. 16 lh + 15 of a step, two segments.
-template <int NT> __global__ __launch_bounds__(256, NT <= 2 ? 4 : 2) void input_conv_kernel(const MfmaParams p, const InputParams q)
+// SEG: 8-byte segments per kernel row (1: S <= 8, 2: S <= 16); a lane's two segments of a step are then the two halves
+// of one kernel row.
+template <int NT, int SEG> __global__ __launch_bounds__(256, NT <= 2 ? 4 : 2) void input_conv_kernel(const MfmaParams p, const InputParams q)
 {
     constexpr int GS = 6;                               // steps whose loads are in flight together
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -51,11 +54,16 @@ template <int NT> __global__ __launch_bounds__(256, NT <= 2 ? 4 : 2) void input_
     const int h0 = ho * p.stride - p.pad, x0 = wo * p.stride - p.pad;
     // The 8 bytes are loaded from a start clamped into the image row and shifted into place;
     // the bytes shifted in are the zeros of the positions left and right of the frame.
-    const int xs = min(max(x0, 0), p.W - 8);
-    const int delta = xs - x0;
-    const bool col_ok = a_ok && delta > -8 && delta < 8;
-    const int shl = delta > 0 ? 8 * delta : 0, shr = delta < 0 ? -8 * delta : 0;
-    const int img_base = n * q.C * p.H * p.W + xs;
+    bool col_ok[SEG];
+    int shl[SEG], shr[SEG], img_base[SEG];
+#pragma unroll
+    for (int g = 0; g < SEG; ++g) {
+        const int xg = x0 + 8 * g, xs = min(max(xg, 0), p.W - 8), delta = xs - xg;
+        col_ok[g] = a_ok && delta > -8 && delta < 8;
+        shl[g] = delta > 0 ? 8 * delta : 0;
+        shr[g] = delta < 0 ? -8 * delta : 0;
+        img_base[g] = n * q.C * p.H * p.W + xs;
+    }
 
     // per-channel parameters of the epilogue: fetched now, their latency hides behind the main loop
     bool cok[NT];
@@ -87,11 +95,13 @@ template <int NT> __global__ __launch_bounds__(256, NT <= 2 ? 4 : 2) void input_
 #pragma unroll
             for (int e = 0; e < 2; ++e) {
                 const int seg = 4 * s + 2 * lh + e;
-                const int c = static_cast<int>((static_cast<float>(seg) + 0.5f) * q.invR);
-                const int h = h0 + (seg - c * p.R);
+                const int sg = SEG == 2 ? e : 0;                   // (4 s + 2 lh is even: segment e of the lane is half e of a kernel row)
+                const int krow = SEG == 2 ? 2 * s + lh : seg;      // kernel row (c, r)
+                const int c = static_cast<int>((static_cast<float>(krow) + 0.5f) * q.invR);
+                const int h = h0 + (krow - c * p.R);
                 uint64_t v = 0;
-                if (col_ok && seg < q.nseg && h >= 0 && h < p.H)
-                    __builtin_memcpy(&v, q.img + img_base + (c * p.H + h) * p.W, 8);
+                if (col_ok[sg] && seg < q.nseg && h >= 0 && h < p.H)
+                    __builtin_memcpy(&v, q.img + img_base[sg] + (c * p.H + h) * p.W, 8);
                 xa[g][e] = v;
             }
 #pragma unroll
@@ -107,7 +117,7 @@ template <int NT> __global__ __launch_bounds__(256, NT <= 2 ? 4 : 2) void input_
             if (s0 + g < q.KS) {
                 // (x & mask) ^ 0x80 per byte as one three-input bit operation (truth table a:0xF0, b:0xCC, c:0xAA)
                 constexpr int AND_XOR = (0xF0 & 0xCC) ^ 0xAA;
-                const uint64_t v0 = (xa[g][0] << shl) >> shr, v1 = (xa[g][1] << shl) >> shr;
+                const uint64_t v0 = (xa[g][0] << shl[0]) >> shr[0], v1 = (xa[g][1] << shl[SEG - 1]) >> shr[SEG - 1];
                 auto signed_bytes = [&](uint32_t x) {
                     return static_cast<int>(__builtin_amdgcn_bitop3_b32(x, q.xmask, 0x80808080u, AND_XOR));
                 };
@@ -247,8 +257,9 @@ __global__ __launch_bounds__(256) void input_weights_kernel(const uint8_t *__res
     const int idx = blockIdx.x * 256 + threadIdx.x;
     if (idx >= Cout * Kp) return;
     const int co = idx / Kp, k = idx - co * Kp;
-    const int seg = k >> 3, s = k & 7;
-    const int c = seg / R, r = seg - c * R;
+    const int nsg = S > 8 ? 2 : 1;                      // 8-byte segments per kernel row
+    const int seg = k >> 3, krow = seg / nsg, s = (seg - krow * nsg) * 8 + (k & 7);
+    const int c = krow / R, r = krow - c * R;
     int v = 0;
     if (c < C && s < S) {
         const uint8_t b = src[((static_cast<size_t>(co) * C + c) * R + r) * S + s];
@@ -267,16 +278,16 @@ __global__ __launch_bounds__(256) void input_cterm_kernel(const int8_t *__restri
     cterm[co] = 128 * sum;
 }
 
-static int64_t input_row_bytes(int64_t Cin, int R) { return round_up(Cin * R * 8, 32); }
+static int64_t input_row_bytes(int64_t Cin, int R, int S) { return round_up(Cin * R * (S > 8 ? 2 : 1) * 8, 32); }
 
 }  // namespace apnn
 
 using namespace apnn;
 
-extern "C" size_t apnn_input_weight_bytes(int64_t Cout, int64_t Cin, int R)
+extern "C" size_t apnn_input_weight_bytes(int64_t Cout, int64_t Cin, int R, int S)
 {
-    if (Cout < 0 || Cin < 1 || R < 1) return 0;
-    return static_cast<size_t>(round_up(Cout * input_row_bytes(Cin, R), 16) + 4 * Cout);
+    if (Cout < 0 || Cin < 1 || R < 1 || S < 1 || S > 16) return 0;
+    return static_cast<size_t>(round_up(Cout * input_row_bytes(Cin, R, S), 16) + 4 * Cout);
 }
 
 extern "C" int apnn_pack_input_weights(const void *src_dev, int64_t Cout, int64_t Cin, int R, int S, int bits,
@@ -286,9 +297,9 @@ extern "C" int apnn_pack_input_weights(const void *src_dev, int64_t Cout, int64_
     const char *who = "apnn_pack_input_weights";
     if (int rc = check_bits_enc(who, "weight", bits, enc)) return rc;
     if (Cout < 0 || Cin < 1 || R < 1 || S < 1) return fail(APNN_ERR_INVALID_ARG, "%s: bad size", who);
-    if (S > 8) return fail(APNN_ERR_UNSUPPORTED, "%s: S = %d, supported up to 8 (one 8-byte K segment per kernel row)", who, S);
+    if (S > 16) return fail(APNN_ERR_UNSUPPORTED, "%s: S = %d, supported up to 16 (two 8-byte K segments per kernel row)", who, S);
     if (bits > 7) return fail(APNN_ERR_UNSUPPORTED, "%s: %d-bit weights do not fit a signed byte", who, bits);
-    const int64_t Kp = input_row_bytes(Cin, R);
+    const int64_t Kp = input_row_bytes(Cin, R, S);
     if (Cout * Kp > 0x7FFFFFFF) return fail(APNN_ERR_INVALID_ARG, "%s: tensor too large", who);
     if (Cout == 0) return APNN_OK;
     if (!src_dev || !dst_dev) return fail(APNN_ERR_INVALID_ARG, "%s: null pointer", who);
@@ -322,7 +333,7 @@ extern "C" int apnn_input_layer(const apnn_layer_desc *desc, const void *W_dev, 
         return fail(APNN_ERR_INVALID_ARG, "%s: bad convolution geometry", who);
     if (d.H + 2 * d.pad < d.R || d.W + 2 * d.pad < d.S)
         return fail(APNN_ERR_INVALID_ARG, "%s: kernel larger than the padded frame", who);
-    if (d.S > 8 || d.W < 8) return fail(APNN_ERR_UNSUPPORTED, "%s: needs S <= 8 and W >= 8 (8-byte K segments)", who);
+    if (d.S > 16 || d.W < 8) return fail(APNN_ERR_UNSUPPORTED, "%s: needs S <= 16 and W >= 8 (8-byte K segments)", who);
     if (d.p > 7) return fail(APNN_ERR_UNSUPPORTED, "%s: %d-bit weights do not fit a signed byte", who, d.p);
     if (d.Cout > 128) return fail(APNN_ERR_UNSUPPORTED, "%s: Cout = %lld, supported up to 128", who, (long long)d.Cout);
     if (L.q_out < 0 || L.q_out > 8) return fail(APNN_ERR_UNSUPPORTED, "%s: q_out = %d, supported 0..8", who, L.q_out);
@@ -369,18 +380,19 @@ extern "C" int apnn_input_layer(const apnn_layer_desc *desc, const void *W_dev, 
     InputParams q{};
     q.img = image_dev;
     q.C = static_cast<int>(d.Cin);
-    q.Kp = static_cast<int>(input_row_bytes(d.Cin, d.R));
+    q.Kp = static_cast<int>(input_row_bytes(d.Cin, d.R, d.S));
     q.KS = q.Kp / 32;
-    q.nseg = static_cast<int>(d.Cin) * d.R;
+    q.nseg = static_cast<int>(d.Cin) * d.R * (d.S > 8 ? 2 : 1);
     q.invR = 1.0f / static_cast<float>(d.R);
     q.xmask = 0x01010101u * ((1u << d.q) - 1u);
     q.w = static_cast<const int8_t *>(W_dev);
     q.cterm = reinterpret_cast<const int32_t *>(q.w + round_up(N * q.Kp, 16));
     const unsigned grid = static_cast<unsigned>(ceil_div(M, 128));
     const int nt = static_cast<int>(ceil_div(N, 32));
-    if (nt == 1) hipLaunchKernelGGL(input_conv_kernel<1>, dim3(grid), dim3(256), 0, as_stream(stream), p, q);
-    else if (nt == 2) hipLaunchKernelGGL(input_conv_kernel<2>, dim3(grid), dim3(256), 0, as_stream(stream), p, q);
-    else if (nt == 3) hipLaunchKernelGGL(input_conv_kernel<3>, dim3(grid), dim3(256), 0, as_stream(stream), p, q);
-    else hipLaunchKernelGGL(input_conv_kernel<4>, dim3(grid), dim3(256), 0, as_stream(stream), p, q);
+    const bool two = d.S > 8;                           // two 8-byte segments per kernel row
+    if (nt == 1) hipLaunchKernelGGL((two ? input_conv_kernel<1, 2> : input_conv_kernel<1, 1>), dim3(grid), dim3(256), 0, as_stream(stream), p, q);
+    else if (nt == 2) hipLaunchKernelGGL((two ? input_conv_kernel<2, 2> : input_conv_kernel<2, 1>), dim3(grid), dim3(256), 0, as_stream(stream), p, q);
+    else if (nt == 3) hipLaunchKernelGGL((two ? input_conv_kernel<3, 2> : input_conv_kernel<3, 1>), dim3(grid), dim3(256), 0, as_stream(stream), p, q);
+    else hipLaunchKernelGGL((two ? input_conv_kernel<4, 2> : input_conv_kernel<4, 1>), dim3(grid), dim3(256), 0, as_stream(stream), p, q);
     return check_launch(who);
 }

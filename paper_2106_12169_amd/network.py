@@ -25,6 +25,7 @@ class PackedNet:
         self.layers, self.batch, self.dev = layers, batch, device
         self.w, self.scale, self.bias, self.buf = {}, {}, {}, {}
         self.geom = {}
+        self._by_name = {L.name: L for L in layers}
         first = layers[0]
         for L in layers:
             if L.kind in ("conv", "fc"):
@@ -32,13 +33,13 @@ class PackedNet:
                 wd = torch.from_numpy(np.ascontiguousarray(wv)).to(device)
                 if L is first:
                     self.w[L.name] = B.apnn_pack_input_weights(wd, L.p, B.ENC_PM1)
-                elif L.kind == "fc":
-                    self.w[L.name] = B.apnn_pack(wd.reshape(L.Cout, -1), L.p, B.ENC_PM1)
+                elif L.kind == "fc" and self._by_name[L.src].kind == "sumpool":
+                    self.w[L.name] = B.apnn_pack(wd.reshape(L.Cout, -1), L.p, B.ENC_PM1)       # matrix operand
                 else:
                     self.w[L.name] = B.apnn_pack_conv_weights(wd, L.p, B.ENC_PM1)
                 self.scale[L.name] = torch.from_numpy(sc).to(device)
                 self.bias[L.name] = torch.from_numpy(bi).to(device)
-            pixels = batch * L.Ho * L.Wo
+            pixels = batch * (L.Ho // 2) * (L.Wo // 2) if (L.kind == "conv" and L.pool) else batch * L.Ho * L.Wo
             if L.kind == "fc":
                 self.buf[L.name] = torch.empty((batch, L.Cout), dtype=torch.int32, device=device)
             elif L.kind == "sumpool":
@@ -50,8 +51,9 @@ class PackedNet:
     def _conv_args(self, L: NetLayer) -> dict:
         d = B.Conv(self.batch, L.H, L.W, L.Cin, L.Cout, L.R, L.S, L.stride, L.pad, L.p, L.q)
         return dict(d=d, W=self.w[L.name], X=self.buf[L.src], q_out=L.q_out, scale=self.scale[L.name],
-                    bias=self.bias[L.name], residual=self.buf[L.res] if L.res else None, q_res=2,
-                    res_scale=L.res_scale, out=self.buf[L.name])
+                    bias=self.bias[L.name], residual=self.buf[L.res] if L.res else None,
+                    q_res=self._by_name[L.res].q_out if L.res else 0,
+                    res_scale=L.res_scale, out=self.buf[L.name], pool=B.POOL_MAX2 if L.pool else B.POOL_NONE)
 
     def forward(self, image: torch.Tensor) -> torch.Tensor:
         """image: batch x 3 x H x W uint8 device tensor -> int32 logits batch x classes."""
@@ -70,7 +72,7 @@ class PackedNet:
             elif L.kind == "conv":
                 nxt = self.layers[i + 1] if i + 1 < len(self.layers) else None
                 if (nxt is not None and nxt.kind == "conv" and nxt.src == L.src
-                        and nxt.res != L.name and L.res != nxt.name):
+                        and nxt.res != L.name and L.res != nxt.name and not L.pool and not nxt.pool):
                     # two convolutions of the same features that do not depend on each other (a down-sampling
                     # block's 3 x 3 convolution and its 1 x 1 shortcut): one call, one launch
                     B.apnn_layer_pair(self._conv_args(L), self._conv_args(nxt))
@@ -83,8 +85,9 @@ class PackedNet:
             elif L.kind == "sumpool":
                 B.apnn_sumpool(self.buf[L.src], self.batch, L.H, L.W, L.Cin, L.q, L.q_out, out=out)
             elif L.kind == "fc":
+                # the pooled sums are a matrix operand; a 1 x 1 feature map is read as one (a 1 x 1 convolution)
                 d = B.Conv(self.batch, 1, 1, L.Cin, L.Cout, 1, 1, 1, 0, L.p, L.q)
-                B.apnn_layer(d, self.w[L.name], self.buf[L.src], is_gemm=True, acc_out=out)
+                B.apnn_layer(d, self.w[L.name], self.buf[L.src], is_gemm=self._by_name[L.src].kind == "sumpool", acc_out=out)
             else:
                 raise ValueError(L.kind)
         return self.buf[self.layers[-1].name]

@@ -221,6 +221,7 @@ class NetLayer:
     q_out: int = 2            # 0 -> int32 output, no requantisation
     res: Optional[str] = None # residual source node (packed q_res-bit codes)
     res_scale: float = 0.0
+    pool: int = 0             # conv only: 1 = 2 x 2 max pooling of the int32 results before the epilogue (Sec. 5.2)
 
     @property
     def Ho(self) -> int:
@@ -270,6 +271,60 @@ def resnet18_layers(image_hw: int = 224, num_classes: int = 1000,
     return L
 
 
+def _plain_chain(image_hw: int, num_classes: int, first, body, fc_width: int) -> List[NetLayer]:
+    """A chain without shortcuts: an input convolution (Cout, kernel, stride, pad), then `body` items that are either
+    ("conv", Cout, kernel, pad, pooled) or ("maxpool", kernel, stride), then three fully connected layers.  The first
+    fully connected layer reads the whole last feature map: a convolution whose kernel covers the frame; the second
+    is a 1 x 1 convolution on the 1 x 1 map; the third produces int32 logits."""
+    L: List[NetLayer] = []
+    cout, k, stride, pad = first
+    L.append(NetLayer("conv1", "conv", "image", 3, cout, image_hw, image_hw, k, k, stride, pad, p=1, q=8, q_out=2))
+    prev, cin, hw = "conv1", cout, L[-1].Ho
+    n = 1
+    for item in body:
+        if item[0] == "conv":
+            _, cout, k, pad, pooled = item
+            n += 1
+            layer = NetLayer(f"conv{n}", "conv", prev, cin, cout, hw, hw, k, k, 1, pad, pool=1 if pooled else 0)
+            L.append(layer)
+            prev, cin, hw = layer.name, cout, (layer.Ho // 2 if pooled else layer.Ho)
+        else:
+            _, k, stride = item
+            layer = NetLayer(f"pool{n}", "maxpool", prev, cin, cin, hw, hw, k, k, stride, 0, q=2, q_out=2)
+            L.append(layer)
+            prev, hw = layer.name, layer.Ho
+    L.append(NetLayer("fc6", "conv", prev, cin, fc_width, hw, hw, hw, hw, 1, 0))
+    L.append(NetLayer("fc7", "conv", "fc6", fc_width, fc_width, 1, 1, 1, 1, 1, 0))
+    L.append(NetLayer("fc8", "fc", "fc7", fc_width, num_classes, 1, 1, 1, 1, 1, 0, p=1, q=2, q_out=0))
+    return L
+
+
+def alexnet_layers(image_hw: int = 224, num_classes: int = 1000,
+                   widths: Tuple[int, int, int, int, int] = (64, 192, 384, 256, 256), fc_width: int = 4096) -> List[NetLayer]:
+    """AlexNet-shaped chain (the paper evaluates an AlexNet variant, Sec. 6.2, without printing its layers; these are
+    the widely used single-tower shapes): 11 x 11 / 4 input convolution on the 8-bit image, 3 x 3 / 2 max pooling on
+    codes after the first, second and fifth convolution, a 5 x 5 and three 3 x 3 convolutions (1-bit weights, 2-bit
+    activations), three fully connected layers."""
+    w = widths
+    body = [("maxpool", 3, 2), ("conv", w[1], 5, 2, False), ("maxpool", 3, 2), ("conv", w[2], 3, 1, False),
+            ("conv", w[3], 3, 1, False), ("conv", w[4], 3, 1, False), ("maxpool", 3, 2)]
+    return _plain_chain(image_hw, num_classes, (w[0], 11, 4, 2), body, fc_width)
+
+
+def vgg16_layers(image_hw: int = 224, num_classes: int = 1000,
+                 widths: Tuple[int, int, int, int, int] = (64, 128, 256, 512, 512), fc_width: int = 4096) -> List[NetLayer]:
+    """VGG-16-shaped chain (the paper's VGG variant is not printed either): thirteen 3 x 3 convolutions in five groups
+    of 2, 2, 3, 3, 3, the last of each group with 2 x 2 max pooling fused into its epilogue (the fusion of Sec. 5.2),
+    three fully connected layers."""
+    body = []
+    for g, (cout, reps) in enumerate(zip(widths, (2, 2, 3, 3, 3))):
+        for r in range(reps):
+            if g == 0 and r == 0:
+                continue                                   # the input convolution
+            body.append(("conv", cout, 3, 1, r == reps - 1))
+    return _plain_chain(image_hw, num_classes, (widths[0], 3, 1, 1), body, fc_width)
+
+
 # Assumed (mean, variance) of one input value by the kind of node that produced
 # it; used only to place the synthetic folded-BN parameters so that every layer
 # keeps using all of its code levels.
@@ -290,7 +345,7 @@ def network_params(layers: List[NetLayer], seed: int = 0):
     value on 2.0 (0.5 for the first layer) plus N(0, 0.1) jitter, less the mean
     contribution of a residual input.
     """
-    kind = {L.name: L.kind for L in layers}
+    kind = {L.name: ("maxpool" if L.kind == "conv" and L.pool else L.kind) for L in layers}
     by_name = {L.name: L for L in layers}
     out = {}
     for i, L in enumerate(layers):
@@ -311,7 +366,10 @@ def network_params(layers: List[NetLayer], seed: int = 0):
         wsum = w.astype(np.float64).sum(axis=(1, 2, 3))
         jitter = 1.0 + 0.1 * normals(20_000 + 100 * seed + i, (L.Cout,)).astype(np.float64)
         a = jitter / math.sqrt(K * v)
-        centre = _FIRST_CENTRE if src_kind == "image" else 2.0
+        # (a layer whose codes go through max pooling sits lower, so that the maximum does not saturate)
+        nxt = [M for M in layers if M.src == L.name]
+        feeds_pool = L.pool or any(M.kind == "maxpool" for M in nxt)
+        centre = _FIRST_CENTRE if (src_kind == "image" or feeds_pool) else 2.0
         if L.res:
             centre -= L.res_scale * _CODE_STATS[0]
         b = centre - a * mu * wsum + normals(30_000 + 100 * seed + i, (L.Cout,), 0.0, 0.1).astype(np.float64)

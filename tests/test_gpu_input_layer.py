@@ -30,6 +30,9 @@ def _weights(seed, shape, p, enc):
     (4, 20, 24, 8, 5, 1, 2, 8, 64, 1, P),      # K of 8 steps: more than one batch of loads
     (3, 12, 8, 3, 3, 1, 4, 8, 64, 1, P),       # narrowest frame; windows entirely left and right of it
     (3, 10, 300, 2, 7, 5, 1, 8, 33, 1, P),     # stride 5, one channel beyond a tile
+    (3, 67, 67, 11, 11, 4, 2, 8, 64, 1, P),    # 11 x 11 stride 4 (the first layer of an AlexNet-shaped network): two segments per kernel row
+    (2, 23, 40, 3, 9, 1, 4, 8, 32, 2, U),      # S = 9: one byte in the second segment
+    (1, 17, 16, 2, 16, 2, 7, 6, 96, 1, P),     # S = 16 = the frame width: windows mostly outside
 ])
 def test_input_layer_accumulators(C, H, W, R, S, stride, pad, bits, Cout, p, enc):
     BS = 2
@@ -128,8 +131,8 @@ def test_input_layer_refusals():
             fn()
         return e.value.status
 
-    w9 = dev(wl.fair_signs(2, (64, 3, 3, 9)))
-    assert status(lambda: B.apnn_pack_input_weights(w9, 1, P)) == 2                 # S > 8
+    w17 = dev(wl.fair_signs(2, (64, 3, 3, 17)))
+    assert status(lambda: B.apnn_pack_input_weights(w17, 1, P)) == 2                # S > 16
     w8 = dev(wl.uniform_codes(3, (64, 3, 3, 3), 8))
     assert status(lambda: B.apnn_pack_input_weights(w8, 8, U)) == 2                 # 8-bit weights
     Wp = B.apnn_pack_input_weights(dev(wl.fair_signs(4, (64, 3, 3, 3))), 1, P)

@@ -1,4 +1,4 @@
-"""GPU parity of the chained residual network: every node's packed codes and
+"""GPU parity of the chained networks (ResNet-18-, AlexNet- and VGG-16-shaped): every node's packed codes and
 the int32 logits bit-exact against the chained oracle."""
 import numpy as np
 import pytest
@@ -21,7 +21,9 @@ def _check_all_nodes(layers, net, want, batch):
             codes, pad = hp.unpack_matrix(got, batch, L.Cout, L.q_out)
             assert np.array_equal(codes, want[L.name]) and pad == 0, L.name
         else:
-            codes, pad = hp.unpack_fmap(got, batch, L.Ho, L.Wo, L.Cout, L.q_out)
+            div = 2 if (L.kind == "conv" and L.pool) else 1
+            codes, pad = hp.unpack_fmap(got, batch, L.Ho // div, L.Wo // div, L.Cout, L.q_out)
+            assert codes.shape == want[L.name].shape, L.name
             assert np.array_equal(codes, want[L.name]) and pad == 0, L.name
 
 
@@ -76,3 +78,38 @@ def test_resnet18_shape_batch32_every_node():
     want = onet.run(layers, params, img)
     _check_all_nodes(layers, net, want, 32)
     assert np.array_equal(logits.cpu().numpy(), want["fc"])
+
+
+@pytest.mark.parametrize("make,kw,hw,batch", [
+    (wl.alexnet_layers, dict(num_classes=50, widths=(32, 64, 96, 64, 64), fc_width=128), 99, 3),
+    (wl.vgg16_layers, dict(num_classes=50, widths=(64, 64, 128, 128, 128), fc_width=128), 32, 3),
+    (wl.vgg16_layers, dict(num_classes=10, widths=(64, 64, 64, 64, 64), fc_width=64), 70, 1),   # odd frames: pooling drops a row and a column
+])
+def test_small_plain_chains_every_node(make, kw, hw, batch):
+    """AlexNet- and VGG-shaped chains (11 x 11 / 4 input layer, 3 x 3 / 2 pooling on codes, 2 x 2 pooling fused into
+    the convolution, fully connected layers as full-frame and 1 x 1 convolutions), reduced sizes, every node."""
+    layers = make(image_hw=hw, **kw)
+    params = wl.network_params(layers, seed=2)
+    img = wl.image_batch(7, batch, hw)
+    net = PackedNet(layers, params, batch)
+    net.forward(torch.from_numpy(img).cuda())
+    torch.cuda.synchronize()
+    want = onet.run(layers, params, img)
+    _check_all_nodes(layers, net, want, batch)
+    for L in layers:                                    # the synthetic parameters keep every layer on all four codes
+        if L.kind == "conv":
+            hist = np.bincount(want[L.name].ravel(), minlength=4) / want[L.name].size
+            assert hist.min() > 0.003, (L.name, hist)
+
+
+@pytest.mark.parametrize("make,batch", [(wl.alexnet_layers, 8), (wl.vgg16_layers, 2)])
+def test_plain_chains_full_size(make, batch):
+    layers = make()
+    params = wl.network_params(layers)
+    img = wl.image_batch(2006, batch, 224)
+    net = PackedNet(layers, params, batch)
+    logits = net.forward(torch.from_numpy(img).cuda())
+    torch.cuda.synchronize()
+    want = onet.run(layers, params, img)
+    _check_all_nodes(layers, net, want, batch)
+    assert np.array_equal(logits.cpu().numpy(), want[layers[-1].name])

@@ -173,3 +173,38 @@ def test_full_size_layer_table():
                 assert short.src == c1.src and (short.Ho, short.Wo, short.Cout) == (c1.Ho, c1.Wo, c1.Cout)
     # 49 codes of at most 3 fit the 8-bit sum
     assert by["sumpool"].H * by["sumpool"].W * 3 < 256
+
+
+def test_plain_chains_pooled_nodes_and_full_frame_layers():
+    """The chains without shortcuts: a convolution with fused 2 x 2 max pooling is the library's pooling of the
+    float64 convolution followed by the epilogue; the first fully connected layer is the product of the flattened
+    (channel, row, column) feature map with the flattened weights; shapes as written here."""
+    layers = wl.vgg16_layers(image_hw=32, num_classes=10, widths=(32, 32, 64, 64, 64), fc_width=96)
+    assert [L.name for L in layers if L.kind == "conv" and L.pool] == ["conv2", "conv4", "conv7", "conv10", "conv13"]
+    assert [(L.name, L.H) for L in layers if L.name in ("conv3", "conv5", "conv8", "conv11", "fc6")] == \
+        [("conv3", 16), ("conv5", 8), ("conv8", 4), ("conv11", 2), ("fc6", 1)]
+    params = wl.network_params(layers)
+    img = wl.image_batch(79, 2, 32)
+    got = onet.run(layers, params, img)
+    by = {L.name: L for L in layers}
+    for name in ("conv2", "conv7"):
+        L = by[name]
+        w, sc, bi = params[name]
+        acc = F.max_pool2d(torch.from_numpy(_conv_f64(w, got[L.src], 1, 1)), 2, 2).numpy().astype(np.int32)
+        codes, _ = oracle.epilogue(acc, sc, bi, 2)
+        assert np.array_equal(codes, got[name]) and codes.shape[2] == L.Ho // 2
+    a = wl.alexnet_layers(image_hw=99, num_classes=10, widths=(32, 64, 96, 64, 64), fc_width=128)
+    assert [(L.name, L.kind, L.H, L.R, L.stride) for L in a[:4]] == \
+        [("conv1", "conv", 99, 11, 4), ("pool1", "maxpool", 24, 3, 2), ("conv2", "conv", 11, 5, 1), ("pool2", "maxpool", 11, 3, 2)]
+    pa = wl.network_params(a)
+    ga = onet.run(a, pa, wl.image_batch(80, 2, 99))
+    L = next(l for l in a if l.name == "fc6")
+    assert (L.H, L.R, L.pad, L.Ho) == (2, 2, 0, 1)
+    w, sc, bi = pa["fc6"]
+    x = ga[L.src].astype(np.float64).reshape(2, -1)                        # (channel, row, column) order
+    acc = (x @ w.astype(np.float64).reshape(w.shape[0], -1).T).astype(np.int32).reshape(2, -1, 1, 1)
+    codes, _ = oracle.epilogue(acc, sc, bi, 2)
+    assert np.array_equal(codes, ga["fc6"])
+    # full-size tables: multiply-accumulates per image of the two shapes
+    macs = lambda Ls: sum(L.Ho * L.Wo * L.Cout * L.Cin * L.R * L.S for L in Ls if L.kind in ("conv", "fc"))
+    assert macs(wl.alexnet_layers()) == 714_188_480 and macs(wl.vgg16_layers()) == 15_470_264_320
