@@ -144,11 +144,10 @@ typedef struct {
  * layout; X_dev: fmap layout; Y_dev: int32 [N][Ho][Wo][Cout].
  * -1/+1 features (Case II with -1/+1 weights, or the mirror of Case III with
  * unsigned weights): a 0 bit means -1, so frame overhang cannot be left to the
- * zero words of the loader; the matrix-instruction form gives every tap a
- * validity word instead and is the only form that implements them.  It needs
- * Cin to be a multiple of 64 and K max|w| < 2^24; otherwise, and whenever that
- * form is switched off, such a call with pad > 0 (or with -1/+1 weights)
- * returns APNN_ERR_UNSUPPORTED. */
+ * zero words of the loader.  Every form of the product gives the features a
+ * made-up validity plane instead (1 inside the frame): the matrix-instruction
+ * form ANDs its operand codes with it, the AND + popcount form counts it as a
+ * second, negative plane (a = 2 bit - validity).  Nothing is refused. */
 int apnn_conv2d(const apnn_conv_desc *desc, const uint32_t *W_dev, const uint32_t *X_dev,
                 int32_t *Y_dev, void *stream);
 
@@ -173,9 +172,9 @@ typedef struct {
                               APNN_POOL_MAX2 maximum, APNN_POOL_SUM2 sum (= 4 x the
                               average; fold 1/4 into scale).  "pixel" below then
                               runs over [N][Ho/2][Wo/2]; incomplete grids of an
-                              odd Ho or Wo are dropped.  Convolutions only, and
-                              only in the matrix-instruction form of the product
-                              (APNN_ERR_UNSUPPORTED otherwise).                       */
+                              odd Ho or Wo are dropped.  Convolutions only
+                              (APNN_ERR_INVALID_ARG with is_gemm); a pooled sum
+                              that may exceed int32: APNN_ERR_OVERFLOW.              */
 } apnn_layer_desc;
 
 /* For every output (pixel, co), Y being the convolution / GEMM result or, with

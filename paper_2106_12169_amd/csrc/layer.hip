@@ -239,22 +239,37 @@ static int run_tile(const Problem &pr, TileParams &p, int vw, void *stream)
     bool use_xor = false;
     p.alpha = 1; p.uA = 0; p.uB = 0; p.c0 = 0;
     const bool a_pm = pr.encA == APNN_ENC_PM1, b_pm = pr.encB == APNN_ENC_PM1;
-    if (p.pool)
-        return fail(APNN_ERR_UNSUPPORTED, "%s: fused pooling needs the matrix-core path (Cin a multiple of 64, 4 K max|w| max|x| below 2^24)", pr.who);
-    if (pr.conv && a_pm && (b_pm || p.pad > 0))
-        return fail(APNN_ERR_UNSUPPORTED,
-                    "%s: -1/+1 features in a convolution need the matrix-core path (Cin a multiple of 64, K below 2^24 / max|w|)",
-                    pr.who);
-    if (a_pm && b_pm) {                 // Case II:  K - 2 popc(XOR)
+    // -1/+1 features whose zero bits would be read as -1 where they must contribute 0 (taps outside the frame):
+    // the kernel gives the feature operand a validity plane that counts negatively (Sec. 4.2 (b), tile_kernel.h).
+    const bool pmz = pr.conv && a_pm && (b_pm || p.pad > 0);
+    int r = pick_tile(pr.M, pr.N);
+    if (pr.conv && vw == 2 && r == 8) r = 4;     // instantiated register tiles per loader width
+    if (pr.conv && vw == 1) r = 2;
+    if (pmz) {
+        // words of K a pass walks (whole LDS read groups), each of which the validity passes count as 32 too many
+        const int64_t nk = ceil_div(p.Kw, kTileKC);
+        const int64_t walked = (nk - 1) * kTileKC + round_up(p.Kw - (nk - 1) * kTileKC, kTileLV);
+        const int64_t weights = (int64_t(1) << pr.PB) - 1;              // sum of the plane weights of the column operand
+        if (3 * 32 * walked * weights >= (int64_t(1) << 31))
+            return fail(APNN_ERR_OVERFLOW, "%s: K too long for the validity-plane form of -1/+1 features", pr.who);
+        p.PA = 2;
+        if (b_pm) {                     // sum (2 a - V)(2 b - 1) = 2 [2 popc(a b) - popc(V b)] + popc(V) - 2 popc(a)
+            p.alpha = 2; p.uA = 1; p.c0 = static_cast<int>(-64 * walked);
+        } else {                        // sum (2 a - V) B_t = 2 popc(a B_t) - popc(V B_t), planes weighted by 2^t
+            p.alpha = 1; p.c0 = static_cast<int>(-32 * walked * weights);
+        }
+    } else if (a_pm && b_pm) {          // Case II:  K - 2 popc(XOR)
         use_xor = true; p.alpha = -2; p.c0 = static_cast<int>(pr.Ktotal);
     } else if (a_pm) {                  // Case III: 2 What X - J X, J X = row sum of the 0/1 operand
         p.alpha = 2; p.uB = -1;
     } else if (b_pm) {
         p.alpha = 2; p.uA = -1;
     }
-    int r = pick_tile(pr.M, pr.N);
-    if (pr.conv && vw == 2 && r == 8) r = 4;     // instantiated register tiles per loader width
-    if (pr.conv && vw == 1) r = 2;
+    if (p.pool == APNN_POOL_SUM2) {     // the sum of a grid must fit the int32 result as well
+        const int64_t ma = a_pm ? 1 : (int64_t(1) << pr.PA) - 1, mb = b_pm ? 1 : (int64_t(1) << pr.PB) - 1;
+        if (4 * pr.Ktotal * ma * mb >= (int64_t(1) << 31))
+            return fail(APNN_ERR_OVERFLOW, "%s: the pooled sum of four results may exceed int32", pr.who);
+    }
     const int64_t tiles = ceil_div(pr.M, 16 * r) * ceil_div(pr.N, 16 * r);
     if (tiles > 0x7FFFFFFF) return fail(APNN_ERR_INVALID_ARG, "%s: problem too large for one launch", pr.who);
     // XCD-aware tile order: among the factorizations of 8 that divide the tile
@@ -274,9 +289,9 @@ static int run_tile(const Problem &pr, TileParams &p, int vw, void *stream)
     const unsigned grid = static_cast<unsigned>(tiles);
     bool ok = false;
     switch (r) {
-        case 8: ok = launch_tile8(p, pr.conv, vw, use_xor, grid, as_stream(stream)); break;
-        case 4: ok = launch_tile4(p, pr.conv, vw, use_xor, grid, as_stream(stream)); break;
-        default: ok = launch_tile2(p, pr.conv, vw, use_xor, grid, as_stream(stream)); break;
+        case 8: ok = launch_tile8(p, pr.conv, vw, use_xor, pmz, grid, as_stream(stream)); break;
+        case 4: ok = launch_tile4(p, pr.conv, vw, use_xor, pmz, grid, as_stream(stream)); break;
+        default: ok = launch_tile2(p, pr.conv, vw, use_xor, pmz, grid, as_stream(stream)); break;
     }
     if (!ok) return fail(APNN_ERR_UNSUPPORTED, "%s: no kernel instance for this configuration", pr.who);
     return check_launch(pr.who);

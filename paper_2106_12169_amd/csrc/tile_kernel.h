@@ -30,6 +30,25 @@
 // for taps outside the frame (zero-contribution padding, valid for Cases I and
 // III, Sec. 4.2 (b)).
 //
+// -1/+1 features (PMZ instances; Sec. 4.2 (b), padding for Case II and for the
+// mirror of Case III): a 0 bit means -1, so zero words would not contribute 0.
+// With V the validity of a position (1 inside the frame) a feature is
+// a = 2 a^ - V, and for a weight plane B_t
+//     sum_k a_k B_t,k = 2 popc(a^ & B_t) - popc(V & B_t):
+// the features become a two-plane operand (plane 1 = the stored bits, which are
+// 0 outside the frame; plane 0 = V, made up by the loader, never read from
+// memory) whose plane 0 counts negatively.  -popc(x) = popc(~x) - 32, so the V
+// passes accumulate popc(~(V & B_t)) with the same two instructions per word
+// and the host folds -32 per word and weight of the pass into c0.  For -1/+1
+// weights the remaining row term popc(V) - 2 popc(a^) comes from the loader-side
+// popcounts that Case III uses.
+//
+// Fused 2 x 2 grid pooling (Sec. 5.2): rows are enumerated as
+// 4 (pooled pixel) + 2 dy + dx, so a grid is four consecutive tile rows: the
+// four (RA >= 4) or two (RA = 2, the other two one lane exchange away) rows a
+// thread holds.  The maximum / sum is taken on the recovered int32 results and
+// the rest of the epilogue runs once per grid.
+//
 // The epilogue (Sec. 4.1 (b) element-wise routine, Sec. 5.2 fusion) runs on the
 // register tile: optional int32 store, fp32 fma with the folded per-channel
 // scale/bias, optional residual, floor/clamp to q_out bits, bit decomposition
@@ -67,7 +86,7 @@ struct TileParams {
     int q_out;
     int NW;              // words per plane row of res/out: N / 32
     int xm, xn;          // 8 XCDs arranged as an xm x xn grid of tile regions (0: plain order)
-    int pool, Hp, Wp;    // fused 2 x 2 grid pooling request (matrix-core kernels only; this kernel has none)
+    int pool, Hp, Wp;    // fused 2 x 2 grid pooling (0 none, 1 maximum, 2 sum) and the pooled frame; M counts 4 rows per pooled pixel
 };
 
 // registers -> LDS in pieces of at most LV words (LDS rows are LV-word aligned)
@@ -107,9 +126,10 @@ template <> struct LdsVec<2> {
 // distinct banks when they read LV-word vectors.
 template <int KC, int RR, int LV> __device__ __forceinline__ int lds_row(int r) { return r * KC + LV * (r / RR); }
 
-template <int RA, int RB, int KC, int VW, int LV, bool CONV, bool XOR>
+template <int RA, int RB, int KC, int VW, int LV, bool CONV, bool XOR, bool PMZ = false>
 __global__ __launch_bounds__(256, (RA * RB >= 64 ? 2 : 4)) void tile_kernel(const TileParams p)
 {
+    static_assert(!PMZ || (CONV && !XOR), "validity-plane features exist for convolutions only");
     constexpr int BM = 16 * RA, BN = 16 * RB;
     constexpr int CH = KC / VW;                       // loader vectors per tile row and chunk
     constexpr int A_VECS = BM * CH, B_VECS = BN * CH;
@@ -169,7 +189,15 @@ __global__ __launch_bounds__(256, (RA * RB >= 64 ? 2 : 4)) void tile_kernel(cons
 #pragma unroll
             for (int u = 0; u < A_SLOTS; ++u) {
                 const int gm = m0 + (tid + 256 * u) / CH;
-                const int wo = gm % p.Wo, ho = (gm / p.Wo) % p.Ho, n = gm / (p.Wo * p.Ho);
+                int wo, ho, n;
+                if (p.pool) {                                      // row = 4 (pooled pixel) + 2 dy + dx
+                    const int g = gm >> 2;
+                    wo = 2 * (g % p.Wp) + (gm & 1);
+                    ho = 2 * ((g / p.Wp) % p.Hp) + ((gm >> 1) & 1);
+                    n = g / (p.Wp * p.Hp);
+                } else {
+                    wo = gm % p.Wo; ho = (gm / p.Wo) % p.Ho; n = gm / (p.Wo * p.Ho);
+                }
                 a_h0[u] = ho * p.stride - p.pad;
                 a_w0[u] = wo * p.stride - p.pad;
                 a_pix[u] = n * p.H * p.W;
@@ -187,7 +215,12 @@ __global__ __launch_bounds__(256, (RA * RB >= 64 ? 2 : 4)) void tile_kernel(cons
                     const int h = a_h0[u] + r, w = a_w0[u] + sc;
                     if (h >= 0 && h < p.H && w >= 0 && w < p.W) {
                         const int64_t pix = a_pix[u] + h * p.W + w;
-                        v = *reinterpret_cast<const Vec *>(p.A + (pix * p.PA + s) * p.Cw + cw);
+                        if (PMZ) {                                 // one stored plane; plane 0 of the operand is the validity
+                            if (s == 0) v = vec_ones<VW>();
+                            else v = *reinterpret_cast<const Vec *>(p.A + pix * p.Cw + cw);
+                        } else {
+                            v = *reinterpret_cast<const Vec *>(p.A + (pix * p.PA + s) * p.Cw + cw);
+                        }
                     }
                 } else {
                     v = *reinterpret_cast<const Vec *>(p.A + (static_cast<int64_t>(gm) * p.PA + s) * p.ldwA + kk);
@@ -229,7 +262,8 @@ __global__ __launch_bounds__(256, (RA * RB >= 64 ? 2 : 4)) void tile_kernel(cons
         auto stage = [&](int buf) {            // registers -> LDS, plus the row-sum popcounts (J X term)
             if (p.uA != 0 && lt == 0) {
 #pragma unroll
-                for (int u = 0; u < A_SLOTS; ++u) rsA[u] += vec_popc(ra[u]) << ls;
+                for (int u = 0; u < A_SLOTS; ++u)
+                    rsA[u] += PMZ ? (ls == 0 ? vec_popc(ra[u]) : -2 * vec_popc(ra[u])) : vec_popc(ra[u]) << ls;
             }
             if (p.uB != 0 && ls == 0) {
 #pragma unroll
@@ -279,14 +313,18 @@ __global__ __launch_bounds__(256, (RA * RB >= 64 ? 2 : 4)) void tile_kernel(cons
 #pragma unroll
                         for (int j = 0; j < RB; ++j) b[nxt][j].load(pb + j * KC + LV * (g + 1));
                     }
+                    // validity plane of -1/+1 features: counts negatively, -popc(x) = popc(~x) - 32 (one three-input
+                    // bit operation either way)
+                    const uint32_t inv = (PMZ && cs == 0) ? ~0u : 0u;
 #pragma unroll
                     for (int i = 0; i < RA; ++i)
 #pragma unroll
                         for (int j = 0; j < RB; ++j)
 #pragma unroll
                             for (int w = 0; w < LV; ++w)
-                                tot[i][j] += XOR ? __popc(a[cur][i].w[w] ^ b[cur][j].w[w])
-                                                 : __popc(a[cur][i].w[w] & b[cur][j].w[w]);
+                                tot[i][j] += XOR   ? __popc(a[cur][i].w[w] ^ b[cur][j].w[w])
+                                             : PMZ ? __popc((a[cur][i].w[w] & b[cur][j].w[w]) ^ inv)
+                                                   : __popc(a[cur][i].w[w] & b[cur][j].w[w]);
                 }
             }
             if (++ck == p.nk) {                // plane pair finished
@@ -334,15 +372,8 @@ __global__ __launch_bounds__(256, (RA * RB >= 64 ? 2 : 4)) void tile_kernel(cons
         const int bit0 = gn0 & 31;
         const float qmax = static_cast<float>((1 << (p.q_out > 0 ? p.q_out : 1)) - 1);
 
-#pragma unroll
-        for (int i = 0; i < RA; ++i) {
-            const int gm = m0 + ty * RA + i;
-            const bool rok = gm < p.M;
-            const int rowfix = p.uA * sRsA[ty * RA + i];
-            int y[RB];
-#pragma unroll
-            for (int j = 0; j < RB; ++j) y[j] = p.alpha * tot[i][j] + rowfix + colfix[j];
-
+        // one output row: optional int32 store, scale/bias, residual, requantise, repack
+        auto finish_row = [&](int gm, bool rok, const int (&y)[RB]) __attribute__((always_inline)) {
             if (p.Y && rok) {
                 int32_t *dst = p.Y + static_cast<int64_t>(gm) * p.N + gn0;
                 if ((RB % 4 == 0) && (p.N % 4 == 0) && gn0 + RB <= p.N) {
@@ -400,6 +431,46 @@ __global__ __launch_bounds__(256, (RA * RB >= 64 ? 2 : 4)) void tile_kernel(cons
                         }
                     }
                 }
+            }
+        };
+
+        // encoding recovery in place (Sec. 3.2)
+#pragma unroll
+        for (int i = 0; i < RA; ++i) {
+            const int rowfix = p.uA * sRsA[ty * RA + i];
+#pragma unroll
+            for (int j = 0; j < RB; ++j) tot[i][j] = p.alpha * tot[i][j] + rowfix + colfix[j];
+        }
+        if (CONV && p.pool) {
+            // 2 x 2 grid pooling of the int32 results: tile rows 4 g .. 4 g + 3 are one grid (Sec. 5.2)
+            auto pool2 = [&](int a, int b) { return p.pool == 1 ? max(a, b) : a + b; };
+            const int Mp = p.M >> 2;
+            if constexpr (RA >= 4) {
+#pragma unroll
+                for (int g = 0; g < RA / 4; ++g) {
+                    int y[RB];
+#pragma unroll
+                    for (int j = 0; j < RB; ++j)
+                        y[j] = pool2(pool2(tot[4 * g][j], tot[4 * g + 1][j]), pool2(tot[4 * g + 2][j], tot[4 * g + 3][j]));
+                    const int gm = (m0 + ty * RA + 4 * g) >> 2;
+                    finish_row(gm, gm < Mp, y);
+                }
+            } else {
+                // two rows here, the other two in the thread 16 lanes away (ty ^ 1); the even one finishes the grid
+                int y[RB];
+#pragma unroll
+                for (int j = 0; j < RB; ++j) {
+                    const int h = pool2(tot[0][j], tot[RA - 1][j]);
+                    y[j] = pool2(h, __shfl_xor(h, 16, 64));
+                }
+                const int gm = (m0 + ty * RA) >> 2;
+                finish_row(gm, gm < Mp && (ty & 1) == 0, y);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < RA; ++i) {
+                const int gm = m0 + ty * RA + i;
+                finish_row(gm, gm < p.M, tot[i]);
             }
         }
     }

@@ -7,10 +7,11 @@ namespace apnn {
 
 // r = per-thread tile edge (8, 4 or 2); block tile is (16 r) x (16 r).
 // vw = loader vector width in words (matrix mode: 4; conv mode: 4, 2 or 1).
+// pmz = convolution over -1/+1 features with a validity plane (tile_kernel.h).
 // Returns false if the combination is not instantiated.
-bool launch_tile8(const TileParams &p, bool conv, int vw, bool use_xor, unsigned grid, hipStream_t st);
-bool launch_tile4(const TileParams &p, bool conv, int vw, bool use_xor, unsigned grid, hipStream_t st);
-bool launch_tile2(const TileParams &p, bool conv, int vw, bool use_xor, unsigned grid, hipStream_t st);
+bool launch_tile8(const TileParams &p, bool conv, int vw, bool use_xor, bool pmz, unsigned grid, hipStream_t st);
+bool launch_tile4(const TileParams &p, bool conv, int vw, bool use_xor, bool pmz, unsigned grid, hipStream_t st);
+bool launch_tile2(const TileParams &p, bool conv, int vw, bool use_xor, bool pmz, unsigned grid, hipStream_t st);
 
 constexpr int kTileKC = 16;   // K words staged per chunk
 #ifndef APNN_TILE_LV

@@ -118,8 +118,6 @@ def test_layer_validation():
     assert layer(q_out=0)[0] == 1                                           # nothing requested
     assert layer(q_out=9)[0] == 2
     assert layer(res=FAKE, q_res=0)[0] == 2
-    # -1/+1 features need the matrix-core form, which one channel word per tap does not allow
-    assert layer(conv=B.Conv(8, 28, 28, 32, 128, 3, 3, 1, 1, encW=B.ENC_PM1, encX=B.ENC_PM1, q=1))[0] == 2
     assert layer(pool=3)[0] == 1                                            # not an apnn_pool value
     assert layer(conv=B.Conv(8, 1, 1, 128, 128, 1, 1, 1, 0), is_gemm=1, pool=1)[0] == 1
     assert layer(conv=B.Conv(8, 2, 2, 128, 128, 7, 7, 1, 1))[0] == 1        # kernel larger than padded frame

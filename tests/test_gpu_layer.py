@@ -75,6 +75,23 @@ def test_conv2d_matches_oracle(tile, Cin, Cout, H, Wd, R, stride, pad, encW, p, 
     assert np.array_equal(got, oracle.conv2d(Wv, encW, p, Xv, U, q, stride, pad))
 
 
+def _force(force):
+    """"auto", a matrix-core block tile ("64", "32split1", "32split4", "32split1wide2") or the AND+popcount kernel
+    with a register tile ("pop8", "pop4", "pop2")."""
+    B.apnn_debug_reset()
+    if force.startswith("pop"):
+        B.apnn_debug_force("MFMA", 0)
+        B.apnn_debug_force("TILE", int(force[3:]))
+    elif force != "auto":
+        B.apnn_debug_force("MFMA_TILE", int(force[:2]))
+        if force.startswith("32split"):
+            B.apnn_debug_force("MFMA_NSPLIT", int(force[7]))
+        if "wide" in force:                             # 32 x 64 / 32 x 128 wave tiles
+            B.apnn_debug_force("MFMA_FN", int(force[-1]))
+
+
+ALL_FORMS = ["auto", "64", "32split1", "32split4", "32split1wide2", "pop8", "pop4", "pop2"]
+
 PM1_FEATURE_CONVS = [
     # Cin, Cout, H, W, R, stride, pad, encW, p, BS
     (64, 64, 14, 14, 3, 1, 1, P, 1, 2),          # Case II with padding: overhang taps must contribute 0, not -1
@@ -83,20 +100,18 @@ PM1_FEATURE_CONVS = [
     (64, 64, 7, 7, 5, 1, 2, U, 2, 1),            # mirrored Case III: unsigned 2-bit weights, two rings of overhang
     (256, 64, 6, 6, 3, 1, 1, U, 1, 1),
     (64, 64, 56, 56, 3, 1, 1, P, 1, 1),          # enough output pixels for the 64 x 64 block tile
+    (32, 64, 10, 9, 3, 1, 1, P, 1, 2),           # one channel word: only the AND+popcount kernel has this shape
+    (96, 32, 7, 8, 3, 2, 2, U, 3, 1),            # three channel words, three weight planes, two rings of padding
+    (160, 64, 5, 5, 4, 1, 2, P, 1, 1),           # K words not a multiple of the LDS read group
 ]
 
 
-@pytest.mark.parametrize("force", ["auto", "64", "32split1", "32split4", "32split1wide2"])
+@pytest.mark.parametrize("force", ALL_FORMS)
 @pytest.mark.parametrize("Cin,Cout,H,Wd,R,stride,pad,encW,p,BS", PM1_FEATURE_CONVS)
 def test_conv_with_pm1_features_matches_oracle(monkeypatch, force, Cin, Cout, H, Wd, R, stride, pad, encW, p, BS):
-    """-1/+1 features (Case II and the mirrored Case III) with zero-contribution padding."""
-    B.apnn_debug_reset()
-    if force != "auto":
-        B.apnn_debug_force("MFMA_TILE", int(force[:2]))
-        if force.startswith("32split"):
-            B.apnn_debug_force("MFMA_NSPLIT", int(force[7]))
-        if "wide" in force:                             # 32 x 64 / 32 x 128 wave tiles
-            B.apnn_debug_force("MFMA_FN", int(force[-1]))
+    """-1/+1 features (Case II and the mirrored Case III) with zero-contribution padding, in the matrix-core form (the
+    overhang taps become FP4 zeros) and in the AND+popcount form (validity plane that counts negatively)."""
+    _force(force)
     Wv = wl.operand(41 + Cin + Cout, Cout, Cin * R * R, p, encW).reshape(Cout, Cin, R, R)
     Xv = wl.fair_signs(42 + H, (BS, Cin, H, Wd))
     d = B.Conv(BS, H, Wd, Cin, Cout, R, R, stride, pad, p, 1, encW, P)
@@ -123,18 +138,27 @@ def test_binary_network_chain():
     assert np.array_equal(Y.cpu().numpy().transpose(0, 3, 1, 2), want)
 
 
-def test_conv_with_pm1_features_refused_without_matrix_path(monkeypatch):
-    """The AND+popcount kernel has no zero-contribution padding for -1/+1 features: the call must fail, not be wrong."""
-    e = torch.zeros(1 << 16, dtype=torch.int32, device="cuda")
+def test_pm1_feature_layer_with_epilogue_on_the_popcount_kernel():
+    """-1/+1 features through the whole fused layer (scale/bias, residual, requantise, repack) on the literal kernel."""
     B.apnn_debug_force("MFMA", 0)
-    for d in (B.Conv(1, 8, 8, 64, 32, 3, 3, 1, 1, 1, 1, P, P), B.Conv(1, 8, 8, 64, 32, 3, 3, 1, 1, 2, 1, U, P)):
-        with pytest.raises(B.ApnnError) as ei:
-            B.apnn_conv2d(d, e, e)
-        assert ei.value.status == 2
-    B.apnn_debug_force("MFMA", -1)
-    with pytest.raises(B.ApnnError) as ei:                      # one channel word: not a matrix-core shape
-        B.apnn_conv2d(B.Conv(1, 8, 8, 32, 32, 3, 3, 1, 1, 1, 1, P, P), e, e)
-    assert ei.value.status == 2
+    BS, Cin, Cout, H = 2, 96, 64, 11
+    Wv = wl.fair_signs(51, (Cout, Cin, 3, 3))
+    Xv = wl.fair_signs(52, (BS, Cin, H, H))
+    scale = (wl.normals(53, (Cout,), 1.0, 0.2) / np.sqrt(9.0 * Cin)).astype(np.float32)
+    bias = wl.normals(54, (Cout,), 1.5, 0.3)
+    res = wl.uniform_codes(55, (BS, Cout, H, H), 2)
+    d = B.Conv(BS, H, H, Cin, Cout, 3, 3, 1, 1, 1, 1, P, P)
+    acc = torch.empty((BS, H, H, Cout), dtype=torch.int32, device="cuda")
+    out = B.apnn_layer(d, B.apnn_pack_conv_weights(dev(Wv), 1, P), B.apnn_pack_fmap(dev(Xv), B.LAYOUT_NCHW, 1, P),
+                       q_out=2, scale=dev(scale), bias=dev(bias), acc_out=acc,
+                       residual=B.apnn_pack_fmap(dev(res), B.LAYOUT_NCHW, 2, U), q_res=2, res_scale=0.5)
+    torch.cuda.synchronize()
+    want_acc = oracle.conv2d(Wv, P, 1, Xv, P, 1, 1, 1)
+    want_codes, _ = oracle.epilogue(want_acc, scale, bias, 2, res=res, res_scale=0.5)
+    assert np.array_equal(acc.cpu().numpy().transpose(0, 3, 1, 2), want_acc)
+    codes, pad_bits = hp.unpack_fmap(hp.words_u32(out), BS, H, H, Cout, 2)
+    assert np.array_equal(codes, want_codes) and pad_bits == 0
+    assert len(np.unique(want_codes)) == 4
 
 
 def _layer_case(BS, Cin, Cout, H, R, stride, pad, q, q_out, with_res, seed):
@@ -298,23 +322,19 @@ def test_patch_packer_geometries(C, H, W, R, S, stride, pad, bits):
     assert (words[:, :, R:] == 0).all()
 
 
-@pytest.mark.parametrize("force", ["auto", "64", "32split1", "32split4", "32split1wide2"])
+@pytest.mark.parametrize("force", ALL_FORMS)
 @pytest.mark.parametrize("mode", [B.POOL_MAX2, B.POOL_SUM2])
 @pytest.mark.parametrize("BS,Cin,Cout,H,Wd,R,stride,pad,with_res", [
     (2, 64, 64, 14, 14, 3, 1, 1, False),
     (1, 128, 96, 9, 11, 3, 1, 1, True),        # odd output frame: the last row and column of results are dropped
     (2, 64, 32, 12, 12, 1, 1, 0, False),       # 1 x 1
     (1, 64, 64, 56, 56, 3, 1, 1, True),        # enough rows for the 64 x 64 block tile
+    (3, 32, 64, 7, 10, 3, 1, 1, True),         # one channel word: only the AND+popcount kernel has this shape
+    (1, 96, 32, 13, 6, 2, 1, 1, False),        # three channel words, 2 x 2 kernel
 ])
 def test_fused_pooling_matches_oracle(monkeypatch, force, mode, BS, Cin, Cout, H, Wd, R, stride, pad, with_res):
     """conv -> 2 x 2 grid pooling of the int32 results -> scale/bias (+ residual) -> requantise -> repack, one kernel."""
-    B.apnn_debug_reset()
-    if force != "auto":
-        B.apnn_debug_force("MFMA_TILE", int(force[:2]))
-        if force.startswith("32split"):
-            B.apnn_debug_force("MFMA_NSPLIT", int(force[7]))
-        if "wide" in force:                             # 32 x 64 / 32 x 128 wave tiles
-            B.apnn_debug_force("MFMA_FN", int(force[-1]))
+    _force(force)
     Wv = wl.fair_signs(71 + Cin, (Cout, Cin, R, R))
     Xv = wl.uniform_codes(72 + H, (BS, Cin, H, Wd), 2)
     d = B.Conv(BS, H, Wd, Cin, Cout, R, R, stride, pad, 1, 2, P, U)
@@ -350,10 +370,6 @@ def test_fused_pooling_refusals(monkeypatch):
     with pytest.raises(B.ApnnError) as ei:                      # GEMM layers have no frame to pool
         B.apnn_layer(B.Conv(8, 1, 1, 64, 64, 1, 1, 1, 0, 1, 2, P, U), e, e, is_gemm=True, q_out=2, scale=f, bias=f, pool=1)
     assert ei.value.status == 1
-    B.apnn_debug_force("MFMA", 0)                        # the AND+popcount kernel does not pool
-    with pytest.raises(B.ApnnError) as ei:
-        B.apnn_layer(d, e, e, q_out=2, scale=f, bias=f, pool=1)
-    assert ei.value.status == 2
 
 
 @pytest.mark.parametrize("force", ["256", "128", "64", "auto"])

@@ -14,7 +14,6 @@ from tests import helpers as hp
 
 pytestmark = pytest.mark.gpu
 U, P = B.ENC_UNSIGNED, B.ENC_PM1
-OUTCOMES = []          # (seed, "computed" | "refused") of this process's sweep
 FORCES = ("auto", "auto", "auto", "64", "32split1", "32split4", "32chunked", "pop4", "pop2", "128", "32split1wide2")
 
 
@@ -22,7 +21,7 @@ def dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
-def _force(monkeypatch, force):
+def _force(force):
     B.apnn_debug_reset()
     if force.startswith("pop"):
         B.apnn_debug_force("MFMA", 0)
@@ -61,10 +60,10 @@ def _draw(rng):
 
 
 @pytest.mark.parametrize("seed", range(int(os.environ.get("APNN_RANDOM_SEEDS", "60"))))   # more seeds for a longer hunt
-def test_random_layer(monkeypatch, seed):
+def test_random_layer(seed):
     rng = np.random.default_rng(7000 + seed)
     c = _draw(rng)
-    _force(monkeypatch, c["force"])
+    _force(c["force"])
     BS, Cin, Cout, H, W, R, S = c["BS"], c["Cin"], c["Cout"], c["H"], c["W"], c["R"], c["S"]
     stride, pad, p, q, encW, encX = c["stride"], c["pad"], c["p"], c["q"], c["encW"], c["encX"]
     Wv = wl.operand(seed, Cout, Cin * R * S, p, encW).reshape(Cout, Cin, R, S)
@@ -86,14 +85,8 @@ def test_random_layer(monkeypatch, seed):
         kw.update(q_out=q_out, scale=dev(scale), bias=dev(bias), float_out=tf)
         if q_res:
             kw.update(residual=B.apnn_pack_fmap(dev(res), B.LAYOUT_NCHW, q_res, U), q_res=q_res, res_scale=0.37)
-    try:
-        out = B.apnn_layer(d, B.apnn_pack_conv_weights(dev(Wv), p, encW), B.apnn_pack_fmap(dev(Xv), B.LAYOUT_NCHW, q, encX), **kw)
-    except B.ApnnError as e:
-        # documented refusals: pooling and -1/+1 features exist only in the matrix-core form
-        assert e.status == 2 and (pool or encX == P), (c, str(e))
-        OUTCOMES.append((seed, "refused"))
-        return
-    OUTCOMES.append((seed, "computed"))
+    # nothing here is refused: every form of the product computes -1/+1 features and fused pooling
+    out = B.apnn_layer(d, B.apnn_pack_conv_weights(dev(Wv), p, encW), B.apnn_pack_fmap(dev(Xv), B.LAYOUT_NCHW, q, encX), **kw)
     torch.cuda.synchronize()
     want_acc = oracle.conv2d(Wv, encW, p, Xv, encX, q, stride, pad)
     if pool:
@@ -106,9 +99,10 @@ def test_random_layer(monkeypatch, seed):
         assert np.array_equal(codes, want_codes) and pad_bits == 0, c
 
 
-def test_sweep_mostly_computes():
-    """The sweep is a parity test only if most draws are computed rather than refused."""
-    if len(OUTCOMES) < 60 or len(OUTCOMES) > 60:
-        pytest.skip("only meaningful after exactly the default sweep has run in this process")
-    refused = sum(1 for _, o in OUTCOMES if o == "refused")
-    assert refused <= 15, OUTCOMES
+def test_sweep_reaches_every_form():
+    """The draws cover pooled layers and -1/+1 features on the AND+popcount kernel as well as on the matrix core."""
+    seen = set()
+    for seed in range(60):
+        c = _draw(np.random.default_rng(7000 + seed))
+        seen.add((c["force"].startswith("pop"), bool(c["pool"]), c["encX"] == P))
+    assert {(True, True, False), (True, False, True), (False, True, False), (False, False, True)} <= seen, seen
