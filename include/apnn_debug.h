@@ -27,6 +27,8 @@
 #ifndef APNN_DEBUG_H
 #define APNN_DEBUG_H
 
+#include <stdint.h>
+
 #ifdef __cplusplus
 extern "C" {
 #endif
@@ -38,6 +40,16 @@ int apnn_debug_force(const char *name, int value);
 
 /* Every override back to what the process environment says. */
 void apnn_debug_reset(void);
+
+/* The block tile edge (square tiles: 32, 64, 128 or 256 output rows and
+ * columns) the dispatch would take for an M x N output: the two-step heuristic
+ * of Sec. 4.3 -- rank the candidates by thread-level parallelism (Eq. 3), keep
+ * the most parallel one if even it stays below its threshold, else take the
+ * highest compute intensity (Eq. 4) whose parallelism reaches its threshold.
+ * matrix_form != 0: the matrix-instruction kernels, else the popcount kernel;
+ * is_conv != 0: convolution operands.  Overrides in force are honoured.
+ * Host only, launches nothing; 0 for an empty output. */
+int apnn_debug_tile_choice(int64_t M, int64_t N, int is_conv, int matrix_form);
 
 #ifdef __cplusplus
 }

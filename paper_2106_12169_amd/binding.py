@@ -29,7 +29,7 @@ EXPORTS = (
     "apnn_pack_patch_weights", "apnn_quantize", "apnn_gemm", "apnn_conv2d", "apnn_layer",
     "apnn_layer_pair", "apnn_input_weight_bytes", "apnn_pack_input_weights", "apnn_input_layer",
     "apnn_fold_bn", "apnn_maxpool", "apnn_sumpool", "apnn_workspace_bytes",
-    "apnn_debug_force", "apnn_debug_reset",
+    "apnn_debug_force", "apnn_debug_reset", "apnn_debug_tile_choice",
 )
 
 
@@ -93,6 +93,7 @@ def lib():
     L.apnn_debug_force.argtypes = [C.c_char_p, i32]
     L.apnn_debug_reset.restype = None
     L.apnn_debug_reset.argtypes = []
+    L.apnn_debug_tile_choice.argtypes = [i64, i64, i32, i32]
     for name in EXPORTS:
         if name not in ("apnn_last_error", "apnn_row_words", "apnn_packed_words", "apnn_fmap_words",
                         "apnn_input_weight_bytes", "apnn_workspace_bytes", "apnn_debug_reset"):
@@ -328,3 +329,8 @@ def apnn_debug_force(name: str, value: int) -> None:
 
 def apnn_debug_reset() -> None:
     lib().apnn_debug_reset()
+
+
+def apnn_debug_tile_choice(M: int, N: int, is_conv: bool = False, matrix_form: bool = True) -> int:
+    """Block tile edge the dispatch would take for an M x N output (Sec. 4.3 heuristic); host only."""
+    return lib().apnn_debug_tile_choice(int(M), int(N), int(is_conv), int(matrix_form))

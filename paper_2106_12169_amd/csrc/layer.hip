@@ -37,18 +37,37 @@ static int ov(Override which)
     return g_override[which].load(std::memory_order_relaxed);
 }
 
-// Tile choice in the spirit of Sec. 4.3 (thread-level parallelism first, then
-// compute intensity), with the constants re-fitted to 256 compute units.
-// The TILE override (8, 4 or 2) replaces the choice (experiments, tests).
+// Tile choice, the two-step heuristic of Sec. 4.3.  Candidates are ranked by thread-level parallelism (Eq. 3; here
+// the number of blocks: plane pairs are batched in time, not space, so p q does not multiply it).  If even the most
+// parallel candidate stays below its threshold it is taken; otherwise the candidate of the highest compute intensity
+// (Eq. 4, 2 bm bn / (bm + bn)) whose parallelism still reaches its threshold.  The paper uses one threshold, T = 64,
+// for its 82 multiprocessors; here each candidate carries the block count from which it measured faster on the 256
+// compute units of MI355X, and the share of its area that must be real output (ragged edges).
+struct TileCandidate { int edge; int64_t min_blocks; double min_useful; };
+
+static int rank_tiles(const TileCandidate *cand, int n, int64_t M, int64_t N)
+{
+    int best = cand[0].edge;                    // the head of the priority queue: highest parallelism
+    double best_ci = 0.0;
+    for (int i = 0; i < n; ++i) {
+        const int64_t e = cand[i].edge, blocks = ceil_div(M, e) * ceil_div(N, e);
+        const double useful = static_cast<double>(M) * N / (static_cast<double>(blocks) * e * e);
+        const double ci = 2.0 * e * e / (e + e);
+        if (i > 0 && (blocks < cand[i].min_blocks || useful < cand[i].min_useful)) continue;
+        if (ci > best_ci) { best_ci = ci; best = cand[i].edge; }
+    }
+    return best;
+}
+
+// AND+popcount kernel.  Measured: the 64 x 64 tile (4 waves per SIMD) matches or beats the 128 x 128 tile (2 waves per
+// SIMD) from 1024^2 outputs up, because the extra resident waves cover block start-up and drain, so 128 is no
+// candidate; below one block per compute unit the 32 x 32 tile recovers parallelism.
+// The TILE override (8, 4 or 2: the per-thread edge) replaces the choice (experiments, tests).
 static int pick_tile(int64_t M, int64_t N)
 {
     if (const int r = ov(OV_TILE); r == 8 || r == 4 || r == 2) return r;
-    // Measured on MI355X: the 64 x 64 tile (4 waves per SIMD) matches or beats the
-    // 128 x 128 tile (2 waves per SIMD) from 1024^2 outputs up, because the extra
-    // resident waves cover block start-up and drain; below one block per compute
-    // unit the 32 x 32 tile recovers thread-level parallelism.
-    const int64_t tiles4 = ceil_div(M, 64) * ceil_div(N, 64);
-    return tiles4 >= 256 ? 4 : 2;
+    static const TileCandidate cand[] = {{32, 0, 0.0}, {64, 256, 0.0}};
+    return rank_tiles(cand, 2, M, N) / 16;
 }
 
 struct Problem {
@@ -76,19 +95,15 @@ static bool mfma_kind(int planes, apnn_encoding enc, int &kind, int &digits, int
 static int pick_mfma_tile(int64_t M, int64_t N, bool conv)
 {
     if (const int t = ov(OV_MFMA_TILE); t == 32 || t == 64 || t == 128 || (t == 256 && !conv)) return t;
-    // largest block tile that still gives most of the 256 compute units a block and
-    // wastes at most a quarter of its area on the ragged edges
-    auto tiles = [&](int t) { return ceil_div(M, t) * ceil_div(N, t); };
-    auto useful = [&](int t) { return static_cast<double>(M) * N / (static_cast<double>(tiles(t)) * t * t); };
     // Convolutions: the lane-private small-layer kernel at every size.  Measured on the ResNet-18 shapes at batch
     // 128 it matches or beats the LDS-staged 64 x 64 and 128 x 128 tiles layer by layer (stage 1: 59 - 73 us against
     // 70 - 87; stage 2: 25 - 42 against 27 - 59), because their gather through registers and LDS costs more
     // instructions than the matrix instructions it feeds.
     if (conv) return 32;
-    if (!conv && tiles(256) >= 192 && useful(256) >= 0.75) return 256;
-    if (tiles(128) >= 192 && useful(128) >= 0.75) return 128;
-    if (tiles(64) >= 1024) return 64;
-    return 32;                                  // small layers: one wave tile per block, K split over its waves
+    // Matrices: 32 (one wave tile per block, K split over its waves) is the head of the queue; larger tiles need most
+    // of the 256 compute units to get a block and at most a quarter of their area wasted on ragged edges.
+    static const TileCandidate cand[] = {{32, 0, 0.0}, {64, 1024, 0.0}, {128, 192, 0.75}, {256, 192, 0.75}};
+    return rank_tiles(cand, 4, M, N);
 }
 
 // ---- 8-bit integer matrix path (matrix operands) -------------------------------------
@@ -494,6 +509,12 @@ extern "C" int apnn_debug_force(const char *name, int value)
             return APNN_OK;
         }
     return fail(APNN_ERR_INVALID_ARG, "apnn_debug_force: unknown override '%s'", name);
+}
+
+extern "C" int apnn_debug_tile_choice(int64_t M, int64_t N, int is_conv, int matrix_form)
+{
+    if (M <= 0 || N <= 0) return 0;
+    return matrix_form ? pick_mfma_tile(M, N, is_conv != 0) : 16 * pick_tile(M, N);
 }
 
 extern "C" void apnn_debug_reset(void)

@@ -49,6 +49,32 @@ def test_workspace_is_never_needed_and_overrides_are_host_only():
     B.apnn_debug_reset()
 
 
+def test_tile_choice_follows_parallelism_first_then_compute_intensity():
+    """Sec. 4.3: the most parallel candidate when even it cannot fill the chip, else the largest tile (highest compute
+    intensity, Eq. 4) whose block count (Eq. 3) still reaches its threshold.  Host only: nothing is launched."""
+    B.apnn_debug_reset()
+    pick = B.apnn_debug_tile_choice
+    for dim in range(128, 1025, 128):                                  # the paper's fully connected shapes, batch 64
+        assert pick(dim, 64) == 32 and pick(dim, 64, matrix_form=False) == 32
+    assert pick(4096, 4096) == 256 and pick(2048, 2048) == 128 and pick(4096, 4096, matrix_form=False) == 64
+    assert pick(1024, 1024, matrix_form=False) == 64 and pick(1000, 1000, matrix_form=False) == 64   # 256 blocks of 64
+    assert pick(1000, 900, matrix_form=False) == 32                    # 240 blocks of 64: parallelism first
+    assert pick(3072, 3072) == 128 and pick(3584, 3584) == 256         # 144 / 196 blocks of 256: threshold 192
+    assert pick(2048, 1024) == 32 and pick(100000, 70) == 64           # 512 blocks of 64: below 1024; 128-wide tiles 45 % empty
+    assert pick(4096, 1024) == 128                                     # 256 blocks of 128
+    assert pick(200000, 100) == 128                                    # ragged N: a 256-wide tile would be 61 % empty
+    prev = 0
+    for n in (64, 256, 1024, 2048, 4096, 8192):                        # never a smaller tile for a larger square
+        t = pick(n, n)
+        assert t >= prev
+        prev = t
+    assert pick(25088, 64, is_conv=True) == 32                         # convolutions: the lane-private kernel
+    B.apnn_debug_force("MFMA_TILE", 64)
+    assert pick(4096, 4096) == 64
+    B.apnn_debug_reset()
+    assert pick(0, 5) == 0
+
+
 def test_sizes():
     assert B.apnn_row_words(1) == 4 and B.apnn_row_words(128) == 4 and B.apnn_row_words(129) == 8
     assert B.apnn_row_words(4096) == 128 and B.apnn_row_words(0) == 0

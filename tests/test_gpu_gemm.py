@@ -136,7 +136,7 @@ def test_config2_full_size_every_element(w, a):
 
 
 @pytest.mark.parametrize("w,a", wl.PAPER_FC_BITS)
-@pytest.mark.parametrize("dim", [128, 640, 1024])
+@pytest.mark.parametrize("dim", wl.PAPER_FC_DIMS)
 def test_paper_fc_shapes(w, a, dim):
     """Fully-connected shapes of the paper's APMM evaluation (batch 64, K = N = dim), default dispatch."""
     wk = wl.paper_fc_workload(w, a, dim)
