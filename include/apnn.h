@@ -249,6 +249,19 @@ int apnn_maxpool(const uint32_t *X_dev, int64_t N, int64_t H, int64_t W, int64_t
 int apnn_sumpool(const uint32_t *X_dev, int64_t N, int64_t H, int64_t W, int64_t C, int bits,
                  int out_bits, uint32_t *out_dev, void *stream);
 
+/* Global sum pooling followed by the fully connected layer that reads it
+ * (the tail of a residual network, Sec. 5.1), in one launch:
+ *   Y[n][co] = sum_c dec(W[co][c]) * sum_{h,w} code[n][h][w][c].
+ * X_dev: packed fmap [N][H][W][bits][C/32] (C a multiple of 32, at most 8192;
+ * N at most 65535);
+ * the sums must fit 8 bits (H*W*(2^bits-1) < 256, else APNN_ERR_OVERFLOW).
+ * W_dev: matrix layout, Cout rows of K = C, p planes, encW as in apnn_gemm.
+ * Y_dev: int32 [N][Cout], no requantisation (the last layer keeps its
+ * accumulators, Sec. 5.1).  Same result as apnn_sumpool to 8 bits followed by
+ * apnn_layer(is_gemm) with acc_out_dev. */
+int apnn_sumpool_fc(const uint32_t *X_dev, int64_t N, int64_t H, int64_t W, int64_t C, int bits,
+                    const uint32_t *W_dev, int64_t Cout, int p, apnn_encoding encW, int32_t *Y_dev, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

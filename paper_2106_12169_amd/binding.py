@@ -28,7 +28,7 @@ EXPORTS = (
     "apnn_pack", "apnn_pack_fmap", "apnn_pack_conv_weights", "apnn_pack_patches",
     "apnn_pack_patch_weights", "apnn_quantize", "apnn_gemm", "apnn_conv2d", "apnn_layer",
     "apnn_layer_pair", "apnn_input_weight_bytes", "apnn_pack_input_weights", "apnn_input_layer",
-    "apnn_fold_bn", "apnn_maxpool", "apnn_sumpool", "apnn_workspace_bytes",
+    "apnn_fold_bn", "apnn_maxpool", "apnn_sumpool", "apnn_sumpool_fc", "apnn_workspace_bytes",
     "apnn_debug_force", "apnn_debug_reset", "apnn_debug_tile_choice",
 )
 
@@ -88,6 +88,7 @@ def lib():
     L.apnn_fold_bn.argtypes = [vp, vp, vp, vp, C.c_double, C.c_double, C.c_double, i64, vp, vp]
     L.apnn_maxpool.argtypes = [vp, i64, i64, i64, i64, i32, i32, i32, i32, vp, vp]
     L.apnn_sumpool.argtypes = [vp, i64, i64, i64, i64, i32, i32, vp, vp]
+    L.apnn_sumpool_fc.argtypes = [vp, i64, i64, i64, i64, i32, vp, i64, i32, i32, vp, vp]
     L.apnn_workspace_bytes.restype = C.c_size_t
     L.apnn_workspace_bytes.argtypes = [C.POINTER(LayerDesc)]
     L.apnn_debug_force.argtypes = [C.c_char_p, i32]
@@ -304,6 +305,15 @@ def apnn_sumpool(X: torch.Tensor, N: int, H: int, W: int, Cc: int, bits: int, ou
     if out is None:
         out = _words(apnn_packed_words(N, Cc, out_bits), X.device)
     _check(lib().apnn_sumpool(_ptr(X), N, H, W, Cc, bits, out_bits, _ptr(out), _stream()))
+    return out
+
+
+def apnn_sumpool_fc(X: torch.Tensor, N: int, H: int, W: int, Cc: int, bits: int, Wp: torch.Tensor, Cout: int, p: int,
+                    encW: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Global sum pooling + fully connected layer in one launch -> int32 [N][Cout]."""
+    if out is None:
+        out = torch.empty((N, Cout), dtype=torch.int32, device=X.device)
+    _check(lib().apnn_sumpool_fc(_ptr(X), N, H, W, Cc, bits, _ptr(Wp), Cout, p, encW, _ptr(out), _stream()))
     return out
 
 

@@ -121,6 +121,135 @@ __global__ __launch_bounds__(64 * NWAVE) void sumpool_kernel(const uint32_t *__r
     }
 }
 
+// Global sum pooling and the fully connected layer that follows it, in one launch (the tail of a residual network,
+// Sec. 5.1): Y[n][co] = sum_c dec(W[co][c]) * (sum over the H x W pixels of code[n][pixel][c]).
+// A block of 256 threads owns one image and a tile of classes.  Phase 1 adds the pixels bit-sliced: a thread keeps an
+// 8-plane counter for the 32 channels of a word and adds each pixel's planes with one full adder per plane (two
+// three-input bit operations), so the sums come out as the bit planes phase 2 wants -- no unpacking, no ballots.  The
+// pixels of a word are shared by up to 8 threads, each with the loads of 8 pixels in flight at once (otherwise the
+// kernel is a chain of memory round trips), and their counters are added through LDS (laid out with lanes on adjacent
+// words: a layout by thread made every access a 64-way bank conflict).  Phase 2: thread (class, eighth of K) runs the
+// AP-Bit plane-pair sum of Sec. 3.1 over its weight words and the sum planes in LDS; the eight partial results meet
+// in an LDS counter.  -1/+1 weights: Case III, 2 S - (sum of the sums), the latter from popcounts of the sum planes.
+// Every block recomputes its image's sums (6 KB of reads): cheaper than a launch, while the blocks are few.
+constexpr int kSumBits = 8;
+
+__device__ __forceinline__ void bitsliced_add(uint32_t (&acc)[kSumBits], const uint32_t (&x)[kSumBits], int xbits)
+{
+    uint32_t carry = 0;
+#pragma unroll
+    for (int b = 0; b < kSumBits; ++b) {
+        const uint32_t xb = b < xbits ? x[b] : 0u;
+        const uint32_t s = acc[b] ^ xb ^ carry;
+        carry = (acc[b] & xb) | (carry & (acc[b] ^ xb));
+        acc[b] = s;
+    }
+}
+
+template <int BITS>      // planes of a code, rounded up to 1, 2, 4 or 8
+__global__ __launch_bounds__(256) void sumpool_fc_kernel(const uint32_t *__restrict__ X, const uint32_t *__restrict__ Wt,
+                                                         int32_t *__restrict__ Y, int HW, int Cw, int bits, int Cout,
+                                                         int class_tile, int p, int ldw, int pm1)
+{
+    constexpr int NT = 256, PIX = 8;                      // threads; pixels whose loads a thread keeps in flight together
+    extern __shared__ uint32_t smem[];                    // sums [8 planes][Cw] | partial counters | total | results
+    const int tid = threadIdx.x, n = blockIdx.y;
+    const int PS = max(1, min(8, NT / Cw));               // threads that share the pixels of a word
+    uint32_t *sums = smem;                                // [kSumBits][Cw]
+    uint32_t *part = sums + kSumBits * Cw;                // [PS][kSumBits][Cw], PS Cw <= 256
+    int *total = reinterpret_cast<int *>(part + kSumBits * NT);
+    int *result = total + 1;                              // [class_tile]
+    if (tid == 0) *total = 0;
+    for (int c = tid; c < class_tile; c += NT) result[c] = 0;
+
+    // phase 2 roles; the weight words of the first class group are fetched now and arrive during phase 1
+    const int c32 = tid & 31, kq = tid >> 5;              // thread (class of a group of 32, words kq, kq + 8, ...)
+    const int cls0 = blockIdx.x * class_tile;
+    uint32_t w_first = 0;
+    if (cls0 + c32 < Cout && kq < Cw) w_first = Wt[(static_cast<int64_t>(cls0 + c32) * p + (p - 1)) * ldw + kq];
+
+    const uint32_t *img = X + static_cast<int64_t>(n) * HW * bits * Cw;
+    for (int base = 0; base < Cw * PS; base += NT) {
+        const int t = base + tid;
+        if (t < Cw * PS) {
+            const int part_id = t / Cw, cw = t - part_id * Cw;              // adjacent threads: adjacent channel words
+            uint32_t acc[kSumBits];
+#pragma unroll
+            for (int b = 0; b < kSumBits; ++b) acc[b] = 0;
+            for (int i0 = part_id; i0 < HW; i0 += PS * PIX) {
+                uint32_t x[PIX][kSumBits];
+#pragma unroll
+                for (int j = 0; j < PIX; ++j) {           // all loads of the group first: one memory round trip
+                    const int i = i0 + j * PS;
+                    const uint32_t *px = img + static_cast<uint32_t>(min(i, HW - 1) * bits) * Cw + cw;
+#pragma unroll
+                    for (int b = 0; b < kSumBits; ++b) x[j][b] = (b < BITS && b < bits) ? px[static_cast<uint32_t>(b * Cw)] : 0u;
+                    if (i >= HW) {
+#pragma unroll
+                        for (int b = 0; b < BITS; ++b) x[j][b] = 0u;
+                    }
+                }
+#pragma unroll
+                for (int j = 0; j < PIX; ++j) bitsliced_add(acc, x[j], BITS);
+            }
+#pragma unroll
+            for (int b = 0; b < kSumBits; ++b) {
+                if (PS > 1) part[(part_id * kSumBits + b) * Cw + cw] = acc[b];
+                else sums[b * Cw + cw] = acc[b];
+            }
+        }
+    }
+    if (PS > 1) {
+        __syncthreads();
+        if (tid < Cw) {
+            uint32_t acc[kSumBits];
+#pragma unroll
+            for (int b = 0; b < kSumBits; ++b) acc[b] = part[b * Cw + tid];
+            for (int k = 1; k < PS; ++k) {
+                uint32_t x[kSumBits];
+#pragma unroll
+                for (int b = 0; b < kSumBits; ++b) x[b] = part[(k * kSumBits + b) * Cw + tid];
+                bitsliced_add(acc, x, kSumBits);
+            }
+#pragma unroll
+            for (int b = 0; b < kSumBits; ++b) sums[b * Cw + tid] = acc[b];
+        }
+    }
+    __syncthreads();
+    if (pm1 && tid < 64) {                                // sum of the sums, for the Case III term: lane = (plane, eighth)
+        const int b = tid & 7;
+        int c = 0;
+        for (int w = tid >> 3; w < Cw; w += 8) c += __popc(sums[b * Cw + w]);
+        atomicAdd(total, c << b);
+    }
+
+    for (int g = 0; g < class_tile; g += 32) {
+        const int cls = cls0 + g + c32;
+        if (cls < Cout) {
+            const uint32_t *wrow = Wt + static_cast<int64_t>(cls) * p * ldw;
+            int y = 0;
+            for (int s = p - 1; s >= 0; --s) {            // Horner over the weight planes, Eq. 1
+                int acc = 0;
+                for (int w = kq; w < Cw; w += 8) {
+                    const uint32_t ww = (g == 0 && s == p - 1 && w == kq) ? w_first : wrow[s * ldw + w];
+#pragma unroll
+                    for (int b = 0; b < kSumBits; ++b) acc += __popc(ww & sums[b * Cw + w]) << b;
+                }
+                y = 2 * y + acc;
+            }
+            atomicAdd(&result[g + c32], y);
+        }
+    }
+    __syncthreads();
+    for (int c = tid; c < class_tile; c += NT) {
+        if (cls0 + c < Cout) {
+            int y = result[c];
+            if (pm1) y = 2 * y - *total;
+            Y[static_cast<int64_t>(n) * Cout + cls0 + c] = y;
+        }
+    }
+}
+
 }  // namespace apnn
 
 using namespace apnn;
@@ -173,4 +302,40 @@ extern "C" int apnn_sumpool(const uint32_t *X_dev, int64_t N, int64_t H, int64_t
         hipLaunchKernelGGL(sumpool_kernel<16>, grid, dim3(1024), 0, as_stream(stream), X_dev, out_dev,
                            static_cast<int>(H * W), static_cast<int>(C), Cw, bits, out_bits, ldw);
     return check_launch("apnn_sumpool");
+}
+
+extern "C" int apnn_sumpool_fc(const uint32_t *X_dev, int64_t N, int64_t H, int64_t W, int64_t C, int bits,
+                               const uint32_t *W_dev, int64_t Cout, int p, apnn_encoding encW, int32_t *Y_dev, void *stream)
+{
+    clear_error();
+    const char *who = "apnn_sumpool_fc";
+    if (int rc = check_bits_enc(who, "code", bits, APNN_ENC_UNSIGNED)) return rc;
+    if (int rc = check_bits_enc(who, "weight", p, encW)) return rc;
+    if (N < 0 || H < 1 || W < 1 || C < 0 || Cout < 0) return fail(APNN_ERR_INVALID_ARG, "%s: bad geometry", who);
+    if (C % 32 != 0 || C == 0)
+        return fail(APNN_ERR_INVALID_ARG, "%s: C = %lld must be a positive multiple of 32 (packed features)", who, (long long)C);
+    if (H * W * ((int64_t(1) << bits) - 1) >= (int64_t(1) << kSumBits))
+        return fail(APNN_ERR_OVERFLOW, "%s: sums of %lld %d-bit codes do not fit %d bits", who, (long long)(H * W), bits, kSumBits);
+    if (int rc = check_int32_range(who, C, p, kSumBits)) return rc;
+    if (N == 0 || Cout == 0) return APNN_OK;
+    if (!Y_dev || !X_dev || !W_dev) return fail(APNN_ERR_INVALID_ARG, "%s: null pointer", who);
+    if (!aligned16(W_dev)) return fail(APNN_ERR_ALIGNMENT, "%s: W_dev must be 16-byte aligned", who);
+    if (C > 8192 || N > 65535 || H * W * bits * (C / 32) > 0x7FFFFFFF)
+        return fail(APNN_ERR_UNSUPPORTED, "%s: at most 8192 channels, 65535 images and 2^31 words per image", who);
+    const int Cw = static_cast<int>(C / 32), ldw = static_cast<int>(apnn_row_words(C));
+    // A block per image and class tile; every block recomputes the image's sums, so the tiles widen with the batch.
+    const int class_tile = N * ceil_div(Cout, 32) <= 2048 ? 32 : 256;
+    // LDS: sum planes, the partial counters of up to 8 threads per word, the total, one result per class of the tile
+    const size_t lds = (static_cast<size_t>(kSumBits) * Cw + kSumBits * 256 + 1 + class_tile) * sizeof(uint32_t);
+    const dim3 grid(static_cast<unsigned>(ceil_div(Cout, class_tile)), static_cast<unsigned>(N));
+    const int pm1 = encW == APNN_ENC_PM1 ? 1 : 0;
+    auto launch = [&](auto kernel) {
+        hipLaunchKernelGGL(kernel, grid, dim3(256), lds, as_stream(stream), X_dev, W_dev, Y_dev, static_cast<int>(H * W), Cw,
+                           bits, static_cast<int>(Cout), class_tile, p, ldw, pm1);
+    };
+    if (bits == 1) launch(sumpool_fc_kernel<1>);
+    else if (bits == 2) launch(sumpool_fc_kernel<2>);
+    else if (bits <= 4) launch(sumpool_fc_kernel<4>);
+    else launch(sumpool_fc_kernel<8>);
+    return check_launch(who);
 }

@@ -21,8 +21,15 @@ from .workloads import NetLayer
 
 
 class PackedNet:
-    def __init__(self, layers: List[NetLayer], params: Dict[str, tuple], batch: int, device="cuda"):
+    def __init__(self, layers: List[NetLayer], params: Dict[str, tuple], batch: int, device="cuda", fuse_tail: bool = True):
+        """fuse_tail: a global sum pooling whose only reader is the last fully connected layer shares that layer's
+        launch (apnn_sumpool_fc); its own buffer is then not written."""
         self.layers, self.batch, self.dev = layers, batch, device
+        self.fused_tail = None
+        if (fuse_tail and len(layers) >= 2 and layers[-1].kind == "fc" and layers[-2].kind == "sumpool"
+                and layers[-1].src == layers[-2].name and layers[-2].q_out == 8 and layers[-2].Cin <= 4096
+                and not any(L.src == layers[-2].name or L.res == layers[-2].name for L in layers[:-1])):
+            self.fused_tail = layers[-2].name
         self.w, self.scale, self.bias, self.buf = {}, {}, {}, {}
         self.geom = {}
         self._by_name = {L.name: L for L in layers}
@@ -83,7 +90,14 @@ class PackedNet:
             elif L.kind == "maxpool":
                 B.apnn_maxpool(self.buf[L.src], self.batch, L.H, L.W, L.Cin, L.q, L.R, L.stride, L.pad, out=out)
             elif L.kind == "sumpool":
+                if L.name == self.fused_tail:
+                    self.launches -= 1                  # computed in the launch of the layer that reads it
+                    continue
                 B.apnn_sumpool(self.buf[L.src], self.batch, L.H, L.W, L.Cin, L.q, L.q_out, out=out)
+            elif L.kind == "fc" and L.src == self.fused_tail:
+                S = self._by_name[L.src]
+                B.apnn_sumpool_fc(self.buf[S.src], self.batch, S.H, S.W, S.Cin, S.q, self.w[L.name], L.Cout, L.p,
+                                  B.ENC_PM1, out=out)
             elif L.kind == "fc":
                 # the pooled sums are a matrix operand; a 1 x 1 feature map is read as one (a 1 x 1 convolution)
                 d = B.Conv(self.batch, 1, 1, L.Cin, L.Cout, 1, 1, 1, 0, L.p, L.q)

@@ -277,6 +277,44 @@ def test_sumpool(BS, C, H):
     assert np.array_equal(codes, oracle.sumpool(Xv)) and pad == 0
 
 
+@pytest.mark.parametrize("BS,C,H,Wd,bits,Cout,p,encW", [
+    (8, 512, 7, 7, 2, 1000, 1, P),       # the tail of the ResNet-18-shaped network
+    (3, 64, 3, 5, 2, 10, 1, P),          # few images, few channel words: many threads share an item's pixels
+    (19, 96, 4, 4, 4, 33, 3, U),         # ragged image group and class tile, unsigned 3-bit weights, 4-bit codes
+    (1, 32, 1, 1, 8, 1, 8, U),           # one pixel, one word, 8 x 8 bits
+    (9, 1024, 2, 2, 1, 70, 2, U),        # 32 words: eight threads each
+    (5, 8192, 3, 3, 3, 64, 1, P),        # the most channels allowed: one thread per word
+    (300, 64, 2, 3, 2, 1000, 1, P),      # a large batch takes class tiles of 256
+])
+def test_sumpool_fc(BS, C, H, Wd, bits, Cout, p, encW):
+    """Global sum pooling + fully connected layer in one launch against the two oracle steps."""
+    Xv = wl.uniform_codes(5 + C, (BS, C, H, Wd), bits)
+    Wv = wl.operand(6 + Cout, Cout, C, p, encW)
+    Y = B.apnn_sumpool_fc(B.apnn_pack_fmap(dev(Xv), B.LAYOUT_NCHW, bits, U), BS, H, Wd, C, bits,
+                          B.apnn_pack(dev(Wv), p, encW), Cout, p, encW,
+                          out=torch.full((BS, Cout), -7, dtype=torch.int32, device="cuda"))
+    torch.cuda.synchronize()
+    sums = oracle.sumpool(Xv)
+    assert np.array_equal(Y.cpu().numpy(), oracle.gemm(sums, U, 8, Wv, encW, p))
+    # and it equals the two library calls it replaces
+    S = B.apnn_sumpool(B.apnn_pack_fmap(dev(Xv), B.LAYOUT_NCHW, bits, U), BS, H, Wd, C, bits, 8)
+    Y2 = torch.empty((BS, Cout), dtype=torch.int32, device="cuda")
+    B.apnn_layer(B.Conv(BS, 1, 1, C, Cout, 1, 1, 1, 0, p, 8, encW, U), B.apnn_pack(dev(Wv), p, encW), S, is_gemm=True, acc_out=Y2)
+    torch.cuda.synchronize()
+    assert torch.equal(Y, Y2)
+
+
+def test_sumpool_fc_refusals():
+    e = torch.zeros(1 << 12, dtype=torch.int32, device="cuda")      # (refused calls launch nothing)
+    for args, status in (((e, 1, 10, 10, 64, 2, e, 10, 1, P), 3),        # 300 does not fit 8 bits
+                         ((e, 1, 2, 2, 48, 2, e, 10, 1, P), 1),          # channels not a multiple of 32
+                         ((e, 1, 2, 2, 16384, 2, e, 10, 1, P), 2),       # too many channels
+                         ((e, 1, 2, 2, 64, 2, e, 10, 2, P), 2)):         # -1/+1 with two planes
+        with pytest.raises(B.ApnnError) as ei:
+            B.apnn_sumpool_fc(*args, out=e)
+        assert ei.value.status == status
+
+
 def test_first_layer_patches_equal_convolution():
     """Input layer: 8-bit image planes x +-1 weights through the receptive-field
     packer and the matrix kernel must equal the 7x7 stride-2 convolution."""
