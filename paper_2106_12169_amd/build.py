@@ -22,7 +22,7 @@ BENCH_LIB = os.path.join(HERE, "libapnn_bench.so")
 BENCH_SOURCES = ["bench_probes.hip"]
 
 # slowest translation units first, so that the parallel build is not left waiting for them
-SOURCES = ["mfma_inst_i8_c8.hip", "mfma_inst_i8_c4.hip", "mfma_inst_i8_c2.hip", "mfma_inst_256_pm1.hip", "mfma_inst_256_u2.hip", "mfma_inst_256_u1.hip",
+SOURCES = ["mfma_inst_i8w_c4.hip", "mfma_inst_i8w_c2.hip", "mfma_inst_i8w_c8.hip", "mfma_inst_i8_c8.hip", "mfma_inst_i8_c4.hip", "mfma_inst_i8_c2.hip", "mfma_inst_256_pm1.hip", "mfma_inst_256_u2.hip", "mfma_inst_256_u1.hip",
            "mfma_inst_128_pm1.hip", "mfma_inst_128_u2.hip", "mfma_inst_128_u1.hip", "mfma_inst_128.hip",
            "mfma_inst_64.hip", "mfma_inst_small.hip", "mfma_inst_small_wide.hip", "mfma_inst_small_pair.hip", "mfma_inst_small_matrix.hip", "mfma_inst_32.hip",
            "tile_inst_8.hip", "tile_inst_4.hip", "tile_inst_2.hip", "layer.hip", "input_layer.hip", "pack.hip", "pool.hip",

@@ -112,7 +112,8 @@ static int pick_mfma_tile(int64_t M, int64_t N, bool conv)
 // is taken where it measured faster on 2048^3 and 4096^3 products: five or more FP4 passes, or four with both
 // operands above two bits (w3a5 24 against 37 us, w4a4 21 against 27; w2a8 stays on the FP4 form, 26 against 27),
 // given enough 128 x 128 tiles to occupy the chip -- and whenever the FP4 form could not be exact (w8a8, K = 2048:
-// 40 us against 1040 us of the AND+popcount kernel).  Override INT8: 0 never, 1 whenever it applies.
+// 40 us against 1040 us of the AND+popcount kernel).  Override INT8: 0 never, 1 whenever it applies, 2 and 3
+// the same with the kernel that shares out the outputs / K among the waves.
 struct I8Operand { int cls; int alpha, off, flipped, pad; uint32_t flip; };
 
 static I8Operand i8_operand(int planes, apnn_encoding enc)
@@ -134,7 +135,7 @@ static bool try_int8(const Problem &pr, MfmaParams &mp, bool fp4_exact, void *st
     const int force = ov(OV_INT8);
     if (force == 0 || ov(OV_MFMA) == 0 || pr.conv || pr.Ktotal <= 0) return false;
     const int64_t tiles = ceil_div(pr.M, 128) * ceil_div(pr.N, 128);
-    if (force != 1) {
+    if (force < 1) {
         const int passes = ((pr.PA + 1) / 2) * ((pr.PB + 1) / 2);
         const bool faster = passes >= 5 || (passes == 4 && pr.PA > 2 && pr.PB > 2);
         if (fp4_exact && (!faster || tiles < 64)) return false;
@@ -157,7 +158,14 @@ static bool try_int8(const Problem &pr, MfmaParams &mp, bool fp4_exact, void *st
                                                    + K * a.off * b.off));
     mp.out_scale = 1.0f;
     mp.xcd_regions = (ceil_div(pr.M, 128) % 2 == 0 && ceil_div(pr.N, 128) % 4 == 0) ? 1 : 0;
-    if (!launch_mfma_i8(mp, a.cls, b.cls, static_cast<unsigned>(tiles), as_stream(stream))) return false;
+    // K shared out among the waves of a block (half the transposition work per matrix instruction, but one wave per
+    // SIMD and four partial results to add): measured faster from K of about 3000 up (2048 x 2048 outputs, w4a4:
+    // K = 2048 22.1 against 20.8 us, 4096 30.8 against 32.1, 8192 49.4 against 56.5; w3a5 4096^3 128 against 136).
+    // Override INT8 = 2: never, 3: whenever the planes fit its LDS.
+    const bool wide = force != 2 && pr.PA + pr.PB <= 10 && !(a.cls == 2 && b.cls == 2) && (force == 3 || K >= 3072);
+    if (!(wide && launch_mfma_i8_wide(mp, a.cls, b.cls, static_cast<unsigned>(tiles), as_stream(stream))) &&
+        !launch_mfma_i8(mp, a.cls, b.cls, static_cast<unsigned>(tiles), as_stream(stream)))
+        return false;
     rc = check_launch(pr.who);
     return true;
 }

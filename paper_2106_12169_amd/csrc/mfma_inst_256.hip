@@ -36,4 +36,19 @@ bool launch_mfma_i8(const MfmaParams &p, int classA, int classB, unsigned grid, 
     }
 }
 
+bool launch_mfma_i8_wide_c2(const MfmaParams &p, int classB, unsigned grid, hipStream_t st);
+bool launch_mfma_i8_wide_c4(const MfmaParams &p, int classB, unsigned grid, hipStream_t st);
+bool launch_mfma_i8_wide_c8(const MfmaParams &p, int classB, unsigned grid, hipStream_t st);
+
+bool launch_mfma_i8_wide(const MfmaParams &p, int classA, int classB, unsigned grid, hipStream_t st)
+{
+    if (p.PA + p.PB > 10) return false;                 // two group buffers of four chunks must fit the 160 KB of LDS
+    switch (classA) {
+        case 0: return launch_mfma_i8_wide_c2(p, classB, grid, st);
+        case 1: return launch_mfma_i8_wide_c4(p, classB, grid, st);
+        case 2: return launch_mfma_i8_wide_c8(p, classB, grid, st);
+        default: return false;
+    }
+}
+
 }  // namespace apnn

@@ -28,6 +28,9 @@ bool launch_mfma_small_matrix(const MfmaParams &p, int kindA, int kindB, int nsp
 
 // 8-bit integer matrix form (matrix operands, 128 x 128 block tile); class: 0, 1, 2 for up to 2, 4, 8 planes.
 bool launch_mfma_i8(const MfmaParams &p, int classA, int classB, unsigned grid, hipStream_t st);
+// The same with K, not the outputs, shared out among the four waves of a block (up to 10 planes in all, not both
+// operands above four); false if there is no such instance.
+bool launch_mfma_i8_wide(const MfmaParams &p, int classA, int classB, unsigned grid, hipStream_t st);
 
 // K words per chunk of each tile size (must match the instances).
 constexpr int mfma_chunk_words(int tile) { return tile == 256 ? 16 : tile == 128 ? 16 : 32; }

@@ -37,6 +37,7 @@ bool launch_mfma_small_conv_pair(const MfmaParams &p0, unsigned grid0, const Mfm
 }
 bool launch_mfma_small_matrix(const MfmaParams &p, int, int, int, unsigned grid, hipStream_t) { return took("small_matrix", p, grid); }
 bool launch_mfma_i8(const MfmaParams &p, int, int, unsigned grid, hipStream_t) { return took("i8", p, grid); }
+bool launch_mfma_i8_wide(const MfmaParams &p, int, int, unsigned grid, hipStream_t) { return took("i8_wide", p, grid); }
 static bool took_tile(const char *name, const TileParams &p, bool pmz, unsigned grid) { g_kernel = name; g_tp = p; g_pmz = pmz; g_grid = grid; return true; }
 bool launch_tile8(const TileParams &p, bool conv, int vw, bool, bool pmz, unsigned grid, hipStream_t) { return conv && vw != 4 ? false : took_tile("tile8", p, pmz, grid); }
 bool launch_tile4(const TileParams &p, bool conv, int vw, bool, bool pmz, unsigned grid, hipStream_t) { return conv && vw == 1 ? false : took_tile("tile4", p, pmz, grid); }
@@ -114,6 +115,10 @@ int main()
     EXPECT(g_kernel == "mfma256" && g_grid == 256 && g_mp.out_scale == 2.0f && g_mp.c0 == 0 && g_mp.xcd_regions == 1);
     (void)apnn_gemm(fw, fw, fy, 2048, 2048, 2048, 3, 5, APNN_ENC_UNSIGNED, APNN_ENC_UNSIGNED, nullptr);  // 6 FP4 passes: one int8 pass
     EXPECT(g_kernel == "i8" && g_grid == 256 && g_mp.accmul == 1 && g_mp.mulA == 0 && g_mp.mulB == 0 && g_mp.c0 == 0);
+    (void)apnn_gemm(fw, fw, fy, 2048, 2048, 4096, 3, 5, APNN_ENC_UNSIGNED, APNN_ENC_UNSIGNED, nullptr);  // long K: shared out among the waves
+    EXPECT(g_kernel == "i8_wide" && g_grid == 256 && g_mp.nk % 4 == 0);
+    (void)apnn_gemm(fw, fw, fy, 2048, 2048, 4096, 5, 6, APNN_ENC_UNSIGNED, APNN_ENC_UNSIGNED, nullptr);  // 11 planes: more than its LDS holds
+    EXPECT(g_kernel == "i8");
     (void)apnn_gemm(fw, fw, fy, 20, 20, 4000, 8, 8, APNN_ENC_UNSIGNED, APNN_ENC_UNSIGNED, nullptr);      // beyond the exact range of FP4
     // bytes are value - 128 on both sides: Y = acc + 128 RA + 128 RB + c0, c0 = -npad 128^2 - 2 * 128 * 128 K + 128^2 K
     EXPECT(g_kernel == "i8" && g_mp.mulA == 128 && g_mp.mulB == 128 && g_mp.flipA == ~0u);

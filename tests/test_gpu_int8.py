@@ -19,38 +19,45 @@ def dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
-def gpu_gemm(W, encW, p, X, encX, q, force=True):
+# INT8 override: 2 = the kernel that shares the outputs out among the waves of a block, 3 = the one that shares K out
+# (where it has an instance: at most 10 planes in all, not both operands above four), 1 = the library's choice of them
+FORMS = [2, 3]
+
+
+def gpu_gemm(W, encW, p, X, encX, q, force=1):
     M, K = W.shape
     N = X.shape[0]
     if force:
-        B.apnn_debug_force("INT8", 1)
+        B.apnn_debug_force("INT8", force)
     Y = torch.full((M, N), -7, dtype=torch.int32, device="cuda")
     B.apnn_gemm(B.apnn_pack(dev(W), p, encW), B.apnn_pack(dev(X), q, encX), M, N, K, p, q, encW, encX, out=Y)
     torch.cuda.synchronize()
     return Y.cpu().numpy()
 
 
+@pytest.mark.parametrize("form", FORMS)
 @pytest.mark.parametrize("p", range(1, 9))
 @pytest.mark.parametrize("q", range(1, 9))
-def test_every_bit_width_pair(p, q):
+def test_every_bit_width_pair(p, q, form):
     M, N, K = 150, 290, 777                               # two row tiles, three column tiles, K not a multiple of 128
     W = wl.uniform_codes(3 * p + K, (M, K), p)
     X = wl.uniform_codes(5 * q + K, (N, K), q)
-    assert np.array_equal(gpu_gemm(W, U, p, X, U, q), oracle.gemm(W, U, p, X, U, q))
+    assert np.array_equal(gpu_gemm(W, U, p, X, U, q, form), oracle.gemm(W, U, p, X, U, q))
 
 
+@pytest.mark.parametrize("form", FORMS)
 @pytest.mark.parametrize("q", range(1, 9))
 @pytest.mark.parametrize("K", [64, 1000])
-def test_pm1_against_every_width_both_ways(q, K):
+def test_pm1_against_every_width_both_ways(q, K, form):
     """Case III and its mirror on this form: twice the sum of the 0/1 plane less the other operand's row sums."""
     M, N = 130, 129
     S = wl.fair_signs(40 + q, (M, K))
     X = wl.uniform_codes(50 + q, (N, K), q)
-    assert np.array_equal(gpu_gemm(S, P, 1, X, U, q), oracle.gemm(S, P, 1, X, U, q))
-    assert np.array_equal(gpu_gemm(X, U, q, S, P, 1), oracle.gemm(X, U, q, S, P, 1))
+    assert np.array_equal(gpu_gemm(S, P, 1, X, U, q, form), oracle.gemm(S, P, 1, X, U, q))
+    assert np.array_equal(gpu_gemm(X, U, q, S, P, 1, form), oracle.gemm(X, U, q, S, P, 1))
     if q == 1:
         T = wl.fair_signs(60, (N, K))
-        assert np.array_equal(gpu_gemm(S, P, 1, T, P, 1), oracle.gemm(S, P, 1, T, P, 1))     # Case II as well
+        assert np.array_equal(gpu_gemm(S, P, 1, T, P, 1, form), oracle.gemm(S, P, 1, T, P, 1))     # Case II as well
 
 
 @pytest.mark.parametrize("M,N,K,p,q", [
@@ -60,26 +67,30 @@ def test_pm1_against_every_width_both_ways(q, K):
     (512, 1024, 1024, 2, 8),
     (1, 1, 1, 8, 8),
     (300, 1, 129, 5, 7),
+    (256, 384, 4096 + 100, 8, 2),  # long K: many groups per wave, ragged last group
+    (130, 140, 128 * 5, 4, 4),     # an odd number of chunks
 ])
-def test_shapes(M, N, K, p, q):
+@pytest.mark.parametrize("form", [1] + FORMS)
+def test_shapes(M, N, K, p, q, form):
     W = wl.uniform_codes(71 + M + p, (M, K), p)
     X = wl.uniform_codes(72 + N + q, (N, K), q)
-    assert np.array_equal(gpu_gemm(W, U, p, X, U, q), oracle.gemm(W, U, p, X, U, q))
+    assert np.array_equal(gpu_gemm(W, U, p, X, U, q, form), oracle.gemm(W, U, p, X, U, q))
 
 
-def test_extremes():
+@pytest.mark.parametrize("form", FORMS)
+def test_extremes(form):
     K = 3000
     W = np.full((140, K), 255, np.uint8)
-    assert (gpu_gemm(W, U, 8, W, U, 8) == K * 255 * 255).all()          # largest accumulators
+    assert (gpu_gemm(W, U, 8, W, U, 8, form) == K * 255 * 255).all()          # largest accumulators
     Z = np.zeros((140, K), np.uint8)
-    assert (gpu_gemm(W, U, 8, Z, U, 8) == 0).all() and (gpu_gemm(Z, U, 8, W, U, 8) == 0).all()
+    assert (gpu_gemm(W, U, 8, Z, U, 8, form) == 0).all() and (gpu_gemm(Z, U, 8, W, U, 8, form) == 0).all()
     H = np.full((140, K), 128, np.uint8)                                  # the byte -128 + 128: both offsets at once
-    assert (gpu_gemm(H, U, 8, H, U, 8) == K * 128 * 128).all()
+    assert (gpu_gemm(H, U, 8, H, U, 8, form) == K * 128 * 128).all()
     ones = np.ones((140, K), np.int8)
-    assert (gpu_gemm(-ones, P, 1, W, U, 8) == -255 * K).all()
+    assert (gpu_gemm(-ones, P, 1, W, U, 8, form) == -255 * K).all()
     K2 = 33024                                                            # the longest K the int32 result allows at 8 x 8 bits
     W2 = np.full((3, K2), 255, np.uint8)
-    assert (gpu_gemm(W2, U, 8, W2, U, 8) == K2 * 255 * 255).all()
+    assert (gpu_gemm(W2, U, 8, W2, U, 8, form) == K2 * 255 * 255).all()
 
 
 def test_taken_when_the_fp4_form_would_not_be_exact():
@@ -91,12 +102,13 @@ def test_taken_when_the_fp4_form_would_not_be_exact():
     assert np.array_equal(gpu_gemm(W8, U, 8, W8, U, 8, force=False), oracle.gemm(W8, U, 8, W8, U, 8))
 
 
+@pytest.mark.parametrize("form", FORMS)
 @pytest.mark.parametrize("M,N", [(257, 131), (2000, 256)])
-def test_ragged_m_writes_nothing_beyond_the_output(M, N):
+def test_ragged_m_writes_nothing_beyond_the_output(M, N, form):
     K = 500
     W = wl.uniform_codes(91, (M, K), 3)
     X = wl.uniform_codes(92, (N, K), 5)
-    B.apnn_debug_force("INT8", 1)
+    B.apnn_debug_force("INT8", form)
     buf = torch.full((M + 200, N), -123456789, dtype=torch.int32, device="cuda")
     B.apnn_gemm(B.apnn_pack(dev(W), 3, U), B.apnn_pack(dev(X), 5, U), M, N, K, 3, 5, U, U, out=buf[:M])
     torch.cuda.synchronize()
@@ -104,11 +116,12 @@ def test_ragged_m_writes_nothing_beyond_the_output(M, N):
     assert (got[M:] == -123456789).all() and np.array_equal(got[:M], oracle.gemm(W, U, 3, X, U, 5))
 
 
+@pytest.mark.parametrize("form", FORMS)
 @pytest.mark.parametrize("q,q_out,with_res,encW,p", [(5, 2, True, P, 1), (8, 3, False, U, 3), (4, 8, False, U, 4)])
-def test_fused_layer(q, q_out, with_res, encW, p):
+def test_fused_layer(q, q_out, with_res, encW, p, form):
     """Fully connected layer with the whole epilogue (scale/bias, residual, requantise, repack, int32 and fp32 side
     outputs) on this form; ragged batch."""
-    B.apnn_debug_force("INT8", 1)
+    B.apnn_debug_force("INT8", form)
     BS, K, Cout = 600, 1000, 320
     Xv = wl.uniform_codes(81 + q, (BS, K), q)
     Wv = wl.operand(82, Cout, K, p, encW)
