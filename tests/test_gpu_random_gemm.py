@@ -20,7 +20,7 @@ def dev(a):
 
 
 @pytest.mark.parametrize("seed", range(int(os.environ.get("APNN_RANDOM_SEEDS", "50"))))   # more seeds for a longer hunt
-def test_random_gemm(monkeypatch, seed):
+def test_random_gemm(seed):
     rng = np.random.default_rng(9000 + seed)
     force = FORCES[rng.integers(len(FORCES))]
     B.apnn_debug_reset()
@@ -39,8 +39,11 @@ def test_random_gemm(monkeypatch, seed):
     K = int(rng.choice([rng.integers(1, 70), rng.integers(70, 700), rng.integers(700, 2100)]))
     encW, p = (P, 1) if rng.integers(2) else (U, int(rng.integers(1, 9)))
     encX, q = (P, 1) if rng.integers(4) == 0 else (U, int(rng.integers(1, 9)))
+    i8 = int(rng.integers(4))                       # 2, 3: the 8-bit integer matrix forms (outputs / K shared out among the waves)
+    if i8 >= 2 and not force.startswith("pop"):
+        B.apnn_debug_force("INT8", i8)
     Wv, Xv = wl.operand(seed, M, K, p, encW), wl.operand(seed + 1, N, K, q, encX)
     Y = torch.full((M, N), -7, dtype=torch.int32, device="cuda")
     B.apnn_gemm(B.apnn_pack(dev(Wv), p, encW), B.apnn_pack(dev(Xv), q, encX), M, N, K, p, q, encW, encX, out=Y)
     torch.cuda.synchronize()
-    assert np.array_equal(Y.cpu().numpy(), oracle.gemm(Wv, encW, p, Xv, encX, q)), (force, M, N, K, p, q, encW, encX)
+    assert np.array_equal(Y.cpu().numpy(), oracle.gemm(Wv, encW, p, Xv, encX, q)), (force, i8, M, N, K, p, q, encW, encX)
