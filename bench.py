@@ -314,8 +314,31 @@ def evidence_mode(B, wl, dev):
     outw = torch.empty(1024 * 256, dtype=torch.int32, device="cuda")
     ops = bench_probes.apnn_probe_valu(1024, 2000, outw)
     t = graph_time(lambda: bench_probes.apnn_probe_valu(1024, 2000, outw), reps=2, replays=3)
+    # the two kernels of the 8-bit integer matrix form over K (2048 x 2048 outputs, 4 x 4 bits)
+    i8_rows = []
+    Y2 = torch.empty((2048, 2048), dtype=torch.int32, device="cuda")
+    for K in (256, 1024, 2048, 4096, 8192):
+        Wp = B.apnn_pack(dev(wl.uniform_codes(3, (2048, K), 4)), 4, wl.ENC_UNSIGNED)
+        Xp = B.apnn_pack(dev(wl.uniform_codes(4, (2048, K), 4)), 4, wl.ENC_UNSIGNED)
+        r = {"K": K}
+        for kernel, force in (("mfma_i8_kernel", 2), ("mfma_i8_wide_kernel", 3)):
+            B.apnn_debug_force("INT8", force)
+            r[f"{kernel}_us"] = round(graph_time(lambda: B.apnn_gemm(Wp, Xp, 2048, 2048, K, 4, 4, wl.ENC_UNSIGNED, wl.ENC_UNSIGNED, out=Y2),
+                                                 reps=5, replays=3) * 1e6, 2)
+        B.apnn_debug_reset()
+        i8_rows.append(r)
+    # time per slot (matrix instruction + n vector instructions) of a SIMD with one and two waves, in cycles of the
+    # nominal 2.4 GHz clock
+    issue = []
+    iters = 4000
+    for waves in (1, 2):
+        for with_matrix, nv in ((True, 0), (False, 8), (False, 16), (True, 4), (True, 8), (True, 16)):
+            ts = graph_time(lambda: bench_probes.apnn_probe_issue(nv, with_matrix, waves, iters, outw), reps=1, replays=3)
+            issue.append({"waves_per_simd": waves, "matrix": with_matrix, "vector": nv,
+                          "nominal_cycles_per_slot": round(ts / (4 * iters * waves) * 2.4e9, 1)})
     print(json.dumps({"mode": "evidence", "outputs": [M, N], "k_scaling": rows,
-                      "valu_and_popcount_chain": {"lane_ops_per_s": ops / t, "frac_of_nominal_peak": ops / t / VALU_PEAK_LANE_OPS}}),
+                      "valu_and_popcount_chain": {"lane_ops_per_s": ops / t, "frac_of_nominal_peak": ops / t / VALU_PEAK_LANE_OPS},
+                      "int8_k_scaling_2048x2048_w4a4": i8_rows, "issue_probe": issue}),
           flush=True)
 
 

@@ -30,6 +30,17 @@ int apnn_probe_valu(int blocks, int iters, uint32_t *out_dev, double *lane_ops, 
  * memory-traffic counters are scaled by. */
 int apnn_probe_copy(const void *src_dev, void *dst_dev, size_t bytes, void *stream);
 
+/* Issue-rate probe: 256 blocks (one per compute unit) of 4 or 8 waves
+ * (waves_per_simd 1 or 2) run `iters` rounds of four slots, a slot being one
+ * FP4 matrix instruction (32 x 32 x 64; left out if with_matrix is 0) followed
+ * by vector_per_matrix (0, 4, 8 or 16) independent vector instructions, all on
+ * registers.  Device time / (4 iters waves_per_simd) is the time a SIMD needs
+ * per slot: it shows how many vector instructions run underneath a matrix
+ * instruction, which is what the kernels' schedules are built around.
+ * out_dev: 256 * 256 * waves_per_simd words of checksums. */
+int apnn_probe_issue(int vector_per_matrix, int with_matrix, int waves_per_simd, int iters, uint32_t *out_dev,
+                     void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -9,7 +9,7 @@ import os
 import torch
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libapnn_bench.so")
-EXPORTS = ("apnn_probe_valu", "apnn_probe_copy")
+EXPORTS = ("apnn_probe_valu", "apnn_probe_copy", "apnn_probe_issue")
 _lib = None
 
 
@@ -21,6 +21,7 @@ def lib():
         L = C.CDLL(LIB_PATH)
         L.apnn_probe_valu.argtypes = [C.c_int, C.c_int, C.c_void_p, C.POINTER(C.c_double), C.c_void_p]
         L.apnn_probe_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.apnn_probe_issue.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
         _lib = L
     return _lib
 
@@ -41,3 +42,8 @@ def apnn_probe_valu(blocks: int, iters: int, out: torch.Tensor) -> float:
 def apnn_probe_copy(src: torch.Tensor, dst: torch.Tensor) -> None:
     _check(lib().apnn_probe_copy(src.data_ptr(), dst.data_ptr(), src.numel() * src.element_size(),
                                  torch.cuda.current_stream().cuda_stream), "apnn_probe_copy")
+
+
+def apnn_probe_issue(vector_per_matrix: int, with_matrix: bool, waves_per_simd: int, iters: int, out: torch.Tensor) -> None:
+    _check(lib().apnn_probe_issue(vector_per_matrix, int(with_matrix), waves_per_simd, iters, out.data_ptr(),
+                                  torch.cuda.current_stream().cuda_stream), "apnn_probe_issue")

@@ -1,7 +1,9 @@
 // Measurement probes (libapnn_bench.so): a register-only AND + popcount chain for the
 // sustained issue rate of the plane-pair inner operation (Sec. 3.1), and a plain copy
-// of known size for scaling the memory-traffic counters.  Nothing of the method is
-// computed here.
+// of known size for scaling the memory-traffic counters, and a loop of one matrix
+// instruction followed by a given number of independent vector instructions, run with
+// one or two waves per SIMD, for the rate at which a SIMD issues them together.
+// Nothing of the method is computed here.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -53,6 +55,51 @@ __global__ __launch_bounds__(256) void probe_copy_kernel(const uint4 *__restrict
 }
 
 
+typedef int v8i_probe_t __attribute__((ext_vector_type(8)));
+typedef float v16f_probe_t __attribute__((ext_vector_type(16)));
+
+// Four accumulator tiles in turn: [FP4 matrix instruction (32 x 32 x 64)] + NV independent vector instructions each.
+template <int NV, bool MFMA> __global__ __launch_bounds__(512) void probe_issue_kernel(uint32_t *__restrict__ out, int iters)
+{
+    v16f_probe_t acc[4];
+    v8i_probe_t a[4], b;
+    for (int j = 0; j < 4; ++j) {
+        for (int r = 0; r < 16; ++r) acc[j][r] = 0.0f;
+        for (int r = 0; r < 8; ++r) a[j][r] = 0x22222222 + 0x01010101 * ((threadIdx.x + j + r) & 1);
+    }
+    for (int r = 0; r < 8; ++r) b[r] = 0x22222222;
+    uint32_t x0 = threadIdx.x, x1 = threadIdx.x * 3, x2 = threadIdx.x * 5, x3 = threadIdx.x * 7;
+    const uint32_t m = 0x33333333u + blockIdx.x;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (MFMA) acc[j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[j], b, acc[j], 4, 4, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
+#pragma unroll
+            for (int v = 0; v < NV; ++v) {
+                if ((v & 3) == 0) asm volatile("v_and_or_b32 %0, %0, %1, %2" : "+v"(x0) : "v"(m), "v"(x1));
+                if ((v & 3) == 1) asm volatile("v_and_or_b32 %0, %0, %1, %2" : "+v"(x1) : "v"(m), "v"(x2));
+                if ((v & 3) == 2) asm volatile("v_and_or_b32 %0, %0, %1, %2" : "+v"(x2) : "v"(m), "v"(x3));
+                if ((v & 3) == 3) asm volatile("v_and_or_b32 %0, %0, %1, %2" : "+v"(x3) : "v"(m), "v"(x0));
+            }
+        }
+    }
+    float s = 0.0f;
+    for (int j = 0; j < 4; ++j)
+        for (int r = 0; r < 16; ++r) s += acc[j][r];
+    out[blockIdx.x * blockDim.x + threadIdx.x] = static_cast<uint32_t>(s) + (x0 ^ x1 ^ x2 ^ x3);
+}
+
+template <bool MFMA> bool launch_issue(int nv, dim3 grid, dim3 block, hipStream_t st, uint32_t *out, int iters)
+{
+    switch (nv) {
+        case 0: hipLaunchKernelGGL((probe_issue_kernel<0, MFMA>), grid, block, 0, st, out, iters); return true;
+        case 4: hipLaunchKernelGGL((probe_issue_kernel<4, MFMA>), grid, block, 0, st, out, iters); return true;
+        case 8: hipLaunchKernelGGL((probe_issue_kernel<8, MFMA>), grid, block, 0, st, out, iters); return true;
+        case 16: hipLaunchKernelGGL((probe_issue_kernel<16, MFMA>), grid, block, 0, st, out, iters); return true;
+        default: return false;
+    }
+}
+
 int launch_status()
 {
     return hipGetLastError() == hipSuccess ? 0 : 5;
@@ -77,5 +124,17 @@ extern "C" int apnn_probe_copy(const void *src_dev, void *dst_dev, size_t bytes,
     const unsigned grid = static_cast<unsigned>(n / 256 + 1 < 8192 ? n / 256 + 1 : 8192);
     hipLaunchKernelGGL(probe_copy_kernel, dim3(grid), dim3(256), 0, static_cast<hipStream_t>(stream),
                        static_cast<const uint4 *>(src_dev), static_cast<uint4 *>(dst_dev), n);
+    return launch_status();
+}
+
+extern "C" int apnn_probe_issue(int vector_per_matrix, int with_matrix, int waves_per_simd, int iters, uint32_t *out_dev,
+                                void *stream)
+{
+    if ((waves_per_simd != 1 && waves_per_simd != 2) || iters < 1 || !out_dev) return 1;
+    if (!with_matrix && vector_per_matrix == 0) return 1;
+    const dim3 grid(256), block(256 * waves_per_simd);   // one block per compute unit: 4 or 8 waves on its 4 SIMDs
+    const bool ok = with_matrix ? launch_issue<true>(vector_per_matrix, grid, block, static_cast<hipStream_t>(stream), out_dev, iters)
+                                : launch_issue<false>(vector_per_matrix, grid, block, static_cast<hipStream_t>(stream), out_dev, iters);
+    if (!ok) return 1;
     return launch_status();
 }
