@@ -5,6 +5,7 @@ import pytest
 import torch
 
 from oracle import network as onet
+from paper_2106_12169_amd import binding as B
 from paper_2106_12169_amd import workloads as wl
 from paper_2106_12169_amd.network import PackedNet
 from tests import helpers as hp
@@ -117,3 +118,21 @@ def test_plain_chains_full_size(make, batch):
     want = onet.run(layers, params, img)
     _check_all_nodes(layers, net, want, batch)
     assert np.array_equal(logits.cpu().numpy(), want[layers[-1].name])
+
+
+@pytest.mark.parametrize("make,kw,hw", [
+    (wl.resnet18_layers, dict(num_classes=100, widths=(32, 64, 96, 128)), 64),
+    (wl.vgg16_layers, dict(num_classes=10, widths=(64, 64, 64, 64, 64), fc_width=64), 38),
+])
+def test_small_networks_on_the_literal_kernel(make, kw, hw):
+    """Every convolution and fully connected layer on the AND + popcount kernel (MFMA override 0): residual blocks,
+    shortcut convolutions, fused 2 x 2 pooling, full-frame and 1 x 1 classifier layers; only the 8-bit input layer
+    keeps its own kernel.  Same codes and logits as the oracle, node by node."""
+    B.apnn_debug_force("MFMA", 0)
+    layers = make(image_hw=hw, **kw)
+    params = wl.network_params(layers, seed=4)
+    img = wl.image_batch(9, 2, hw)
+    net = PackedNet(layers, params, 2, fuse_tail=False)
+    net.forward(torch.from_numpy(img).cuda())
+    torch.cuda.synchronize()
+    _check_all_nodes(layers, net, onet.run(layers, params, img), 2)
