@@ -336,7 +336,18 @@ def evidence_mode(B, wl, dev):
             ts = graph_time(lambda: bench_probes.apnn_probe_issue(nv, with_matrix, waves, iters, outw), reps=1, replays=3)
             issue.append({"waves_per_simd": waves, "matrix": with_matrix, "vector": nv,
                           "nominal_cycles_per_slot": round(ts / (4 * iters * waves) * 2.4e9, 1)})
+    # a launch that does (almost) nothing, and a plain 256 MiB copy: the fixed cost of a launch and the HBM rate
+    tiny_s, tiny_d = torch.zeros(16, dtype=torch.uint8, device="cuda"), torch.zeros(16, dtype=torch.uint8, device="cuda")
+    t_empty = graph_time(lambda: bench_probes.apnn_probe_copy(tiny_s, tiny_d), reps=20, replays=5)
+    big_s = torch.zeros(1 << 28, dtype=torch.uint8, device="cuda")
+    big_d = torch.empty_like(big_s)
+    t_copy = graph_time(lambda: bench_probes.apnn_probe_copy(big_s, big_d), reps=2, replays=3)
+    fill = torch.empty(1 << 26, dtype=torch.uint8, device="cuda")
+    t_fill = graph_time(lambda: fill.zero_(), reps=5, replays=3)
     print(json.dumps({"mode": "evidence", "outputs": [M, N], "k_scaling": rows,
+                      "launch_of_16_bytes_us": round(t_empty * 1e6, 2),
+                      "copy_256MiB": {"us": round(t_copy * 1e6, 1), "read_plus_write_TBps": round(2 * (1 << 28) / t_copy / 1e12, 2)},
+                      "fill_64MiB_us": round(t_fill * 1e6, 2),
                       "valu_and_popcount_chain": {"lane_ops_per_s": ops / t, "frac_of_nominal_peak": ops / t / VALU_PEAK_LANE_OPS},
                       "int8_k_scaling_2048x2048_w4a4": i8_rows, "issue_probe": issue}),
           flush=True)
