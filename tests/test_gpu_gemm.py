@@ -27,7 +27,7 @@ def gpu_gemm(W, encW, p, X, encX, q):
 
 
 @pytest.fixture(params=["auto", "pop8", "pop4", "pop2", "mfma32", "mfma32split1", "mfma32split4", "mfma32chunked", "mfma64", "mfma128", "mfma256"])
-def tile(request, monkeypatch):
+def tile(request):
     """Kernel path under test: the library's own choice, the AND+popcount kernel with
     each register tile, or the FP4 matrix-core kernel with each block tile."""
     B.apnn_debug_reset()
@@ -169,7 +169,7 @@ def test_large_tile_kernel_full_width_sampled(encW, p, encX, q, K):
     ("256", 1024, 2048, 64),       # 4 x 8 tiles of 256
     ("256", 512, 1000, 200),       # 2 x 4, ragged N
 ])
-def test_large_tile_kernel_region_order(monkeypatch, force, M, N, K):
+def test_large_tile_kernel_region_order(force, M, N, K):
     """Tile grids that divide into 2 x 4 regions are walked region by region (one per XCD): every tile must still be
     computed exactly once, whatever the grid."""
     B.apnn_debug_reset()

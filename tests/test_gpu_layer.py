@@ -19,7 +19,7 @@ def dev(a):
 
 
 @pytest.fixture(params=["auto", "pop8", "pop4", "pop2", "mfma32", "mfma32split1", "mfma32split4", "mfma32split1wide2", "mfma32chunked", "mfma64", "mfma128", "mfma256"])
-def tile(request, monkeypatch):
+def tile(request):
     """Kernel path under test: the library's own choice, the AND+popcount kernel with
     each register tile, or the FP4 matrix-core kernel with each block tile."""
     B.apnn_debug_reset()
@@ -108,7 +108,7 @@ PM1_FEATURE_CONVS = [
 
 @pytest.mark.parametrize("force", ALL_FORMS)
 @pytest.mark.parametrize("Cin,Cout,H,Wd,R,stride,pad,encW,p,BS", PM1_FEATURE_CONVS)
-def test_conv_with_pm1_features_matches_oracle(monkeypatch, force, Cin, Cout, H, Wd, R, stride, pad, encW, p, BS):
+def test_conv_with_pm1_features_matches_oracle(force, Cin, Cout, H, Wd, R, stride, pad, encW, p, BS):
     """-1/+1 features (Case II and the mirrored Case III) with zero-contribution padding, in the matrix-core form (the
     overhang taps become FP4 zeros) and in the AND+popcount form (validity plane that counts negatively)."""
     _force(force)
@@ -370,7 +370,7 @@ def test_patch_packer_geometries(C, H, W, R, S, stride, pad, bits):
     (3, 32, 64, 7, 10, 3, 1, 1, True),         # one channel word: only the AND+popcount kernel has this shape
     (1, 96, 32, 13, 6, 2, 1, 1, False),        # three channel words, 2 x 2 kernel
 ])
-def test_fused_pooling_matches_oracle(monkeypatch, force, mode, BS, Cin, Cout, H, Wd, R, stride, pad, with_res):
+def test_fused_pooling_matches_oracle(force, mode, BS, Cin, Cout, H, Wd, R, stride, pad, with_res):
     """conv -> 2 x 2 grid pooling of the int32 results -> scale/bias (+ residual) -> requantise -> repack, one kernel."""
     _force(force)
     Wv = wl.fair_signs(71 + Cin, (Cout, Cin, R, R))
@@ -398,7 +398,7 @@ def test_fused_pooling_matches_oracle(monkeypatch, force, mode, BS, Cin, Cout, H
     assert len(np.unique(want_codes)) == 4
 
 
-def test_fused_pooling_refusals(monkeypatch):
+def test_fused_pooling_refusals():
     e = torch.zeros(1 << 16, dtype=torch.int32, device="cuda")
     f = torch.zeros(64, dtype=torch.float32, device="cuda")
     d = B.Conv(1, 8, 8, 64, 64, 3, 3, 1, 1, 1, 2, P, U)
@@ -412,7 +412,7 @@ def test_fused_pooling_refusals(monkeypatch):
 
 @pytest.mark.parametrize("force", ["256", "128", "64", "auto"])
 @pytest.mark.parametrize("q,q_out,with_res", [(2, 2, True), (4, 3, False), (1, 1, False)])
-def test_fused_gemm_layer_all_matrix_tiles(monkeypatch, force, q, q_out, with_res):
+def test_fused_gemm_layer_all_matrix_tiles(force, q, q_out, with_res):
     """Fully-connected layer with the whole epilogue (scale/bias, residual, requantise, repack, int32 and fp32 side
     outputs) through every matrix-operand kernel, the large-tile one included; ragged batch."""
     B.apnn_debug_reset()

@@ -18,7 +18,7 @@ def dev(a):
 
 
 @pytest.fixture(autouse=True, params=["32", "32split1", "32split4", "32chunked", "64", "128", "256"])
-def mfma_tile(request, monkeypatch):
+def mfma_tile(request):
     B.apnn_debug_force("MFMA", -1)
     B.apnn_debug_force("MFMA_SMALL", -1)
     B.apnn_debug_force("MFMA_TILE", int(request.param[:2] if request.param.startswith("32") else request.param))
@@ -71,7 +71,7 @@ def test_mfma_extremes():
     assert (gpu_gemm(W8, U, 8, W8, U, 8) == 255 * 255 * 255).all()
 
 
-def test_mfma_falls_back_when_fp32_would_not_be_exact(monkeypatch):
+def test_mfma_falls_back_when_fp32_would_not_be_exact():
     """K * 3 * 3 >= 2^24: the dispatcher must take the integer kernel; the result stays exact."""
     K = 1 << 21
     W = np.full((4, K), 3, np.uint8)
