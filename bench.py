@@ -200,6 +200,8 @@ def main():
     want = Xv.astype(np.int64) @ Wv.astype(np.int64).sum(0)
     assert np.array_equal(colsum, want), "timed output failed its column-sum check"
 
+    # the same step (both launches) replayed as a HIP graph: what the launch gaps of the eager loop cost (not `value`)
+    step_graph_s = graph_time(step, reps=10, replays=5)
     traffic, traffic_src = profile_traffic("mfma_big_kernel_gemm_w1a2_4096_hbm_counters.txt")
     pop_traffic, pop_traffic_src = profile_traffic("tile_kernel_gemm_w1a2_4096_hbm_counters.txt")
     out = {
@@ -212,7 +214,9 @@ def main():
         "dtype": "fp4 e2m1 products of packed bit planes, fp32 accumulate (exact: K max|w| max|x| = 12288 < 2^24), int32 out",
         "data": "synthetic",
         "config": {"workload": "config1: w1a2 GEMM M=N=K=4096, +-1 weights x unsigned 2-bit activations, int32 out",
-                   "step": "apnn_pack(activations) + apnn_gemm", "seeds": [wk.seedW, wk.seedX]},
+                   "step": "apnn_pack(activations) + apnn_gemm", "seeds": [wk.seedW, wk.seedX],
+                   "launch": "eager, one library call per kernel; the same step replayed as a HIP graph takes step_graph_replay_ms"},
+        "step_graph_replay_ms": round(step_graph_s * 1e3, 5),
         "roofline": {
             "bound": "mfma", "kernel": "mfma_big_kernel<PM1,U2> (v_mfma_scale_f32_32x32x64_f8f6f4, FP4 E2M1)",
             "achieved": round(flops / gemm_s / 1e12, 1), "peak": MFMA_FP4_PEAK / 1e12, "unit": "TFLOP/s",

@@ -435,7 +435,8 @@ __global__ __launch_bounds__(64 * NWM * NWN, FM * FN >= 16 ? 1 : 2) void mfma_bi
 #pragma unroll
         for (int j = 0; j < FN; ++j) voffY[j] = (vbase + 128u * j) | (gn0 + 32 * j < p.N ? 0u : OUT_OF_RANGE);
         static_for<FM * FN * 16>([&](auto c) {
-            constexpr int i = decltype(c)::value / (FN * 16), j = decltype(c)::value / 16 % FN, r = decltype(c)::value % 16;
+            // (the FN tiles of a row one after the other: FN x 128 contiguous bytes of a row leave together)
+            constexpr int i = decltype(c)::value / (FN * 16), r = decltype(c)::value / FN % 16, j = decltype(c)::value % FN;
             constexpr int row = i * 32 + 8 * (r >> 2) + (r & 3);
             __builtin_amdgcn_raw_buffer_store_b32(static_cast<int>(acc[i][j][r]) + p.c0, rsrcY,
                                                   voffY[j] + 4u * row * static_cast<uint32_t>(p.N), 0, 0);
