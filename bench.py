@@ -244,7 +244,9 @@ def main():
     out["roofline_pack_kernel"] = {"bound": "hbm", "kernel": "pack_rows_kernel (activations of the step)",
                                    "achieved": round(pack_bytes / t_pack / 1e9, 1), "peak": HBM_PEAK / 1e9, "unit": "GB/s",
                                    "frac": round(pack_bytes / t_pack / HBM_PEAK, 4), "kernel_us": round(t_pack * 1e6, 2),
-                                   "algorithmic_bytes": pack_bytes}
+                                   "algorithmic_bytes": pack_bytes,
+                                   "what": "device time per launch by graph replay, of which about 1.9 us is the launch itself "
+                                           "(bench.py --evidence, launch_of_16_bytes_us): 20 MiB in what remains is the HBM rate"}
 
     if not args.no_cpu:
         import oracle
