@@ -109,10 +109,11 @@ static int pick_mfma_tile(int64_t M, int64_t N, bool conv)
 // ---- 8-bit integer matrix path (matrix operands) -------------------------------------
 // One pass over K whatever p and q are (the FP4 form needs ceil(p/2) ceil(q/2)), exact for every K the int32
 // result allows.  Its cost is the transposition of plane words into bytes, which grows with the plane counts, so it
-// is taken where it measured faster on 2048^3 and 4096^3 products: five or more FP4 passes, or four with both
-// operands above two bits (w3a5 24 against 37 us, w4a4 21 against 27; w2a8 stays on the FP4 form, 26 against 27),
-// given enough 128 x 128 tiles to occupy the chip -- and whenever the FP4 form could not be exact (w8a8, K = 2048:
-// 40 us against 1040 us of the AND+popcount kernel).  Override INT8: 0 never, 1 whenever it applies, 2 and 3
+// is taken where it measured faster on 2048^3 ... 4096^3 products: five or more FP4 passes; four with both operands
+// above two bits (w3a5 24 against 37 us, w4a4 21 against 27 at 2048^3); four with a narrow operand (w2a8, w1a7) only up
+// to one 128 x 128 tile per compute unit (2048^3: 24.7 against 27.0 us; 3072^3: 89 against 81, 4096^3: 144 against
+// 117, where the FP4 form runs its 256 x 256 tiles) -- given enough tiles to occupy the chip, and whenever the FP4
+// form could not be exact (w8a8, K = 2048: 40 us against 1040 us of the AND+popcount kernel).  Override INT8: 0 never, 1 whenever it applies, 2 and 3
 // the same with the kernel that shares out the outputs / K among the waves.
 struct I8Operand { int cls; int alpha, off, flipped, pad; uint32_t flip; };
 
@@ -137,7 +138,7 @@ static bool try_int8(const Problem &pr, MfmaParams &mp, bool fp4_exact, void *st
     const int64_t tiles = ceil_div(pr.M, 128) * ceil_div(pr.N, 128);
     if (force < 1) {
         const int passes = ((pr.PA + 1) / 2) * ((pr.PB + 1) / 2);
-        const bool faster = passes >= 5 || (passes == 4 && pr.PA > 2 && pr.PB > 2);
+        const bool faster = passes >= 5 || (passes == 4 && ((pr.PA > 2 && pr.PB > 2) || tiles <= 256));
         if (fp4_exact && (!faster || tiles < 64)) return false;
     }
     const int64_t lim = int64_t(1) << 31;       // operands and output are addressed with 31-bit byte offsets
