@@ -118,12 +118,18 @@ def main():
     ap.add_argument("--reps", type=int, default=10)
     ap.add_argument("--zeros", action="store_true", help="--gemm with all-zero operand planes")
     ap.add_argument("--evidence", action="store_true")
+    ap.add_argument("--phases", action="store_true",
+                    help="phase time stamps of mfma_big_kernel on config 1; needs the library built with -DAPNN_BIG_TIMING "
+                         "(python -c \"from paper_2106_12169_amd import build; build.build(True, ['-DAPNN_BIG_TIMING=1'])\")")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
 
     import numpy as np
     import torch
+    if args.phases:                               # (the instrumented library reads the address when apnn_gemm is called)
+        phase_buf = torch.zeros(256 * 4 * 8, dtype=torch.int64, device="cuda")
+        os.environ["APNN_DBG_PTR"] = str(phase_buf.data_ptr())
     from paper_2106_12169_amd import binding as B
     from paper_2106_12169_amd import workloads as wl
 
@@ -145,6 +151,8 @@ def main():
         return gemm_mode(args, B, wl, dev)
     if args.evidence:
         return evidence_mode(B, wl, dev)
+    if args.phases:
+        return phases_mode(B, wl, dev, phase_buf)
 
     wk = wl.CONFIG1
     Wv, Xv = wk.weights(), wk.activations()
@@ -292,6 +300,31 @@ def gemm_mode(args, B, wl, dev):
     t = graph_time(call, reps=10, replays=3)
     print(json.dumps({"mode": "gemm", "shape": [M, N, K], "bits": [p, q], "enc": [encW, encX], "force": args.force,
                       "zeros": bool(args.zeros), "graph_replay_us": round(t * 1e6, 2)}), flush=True)
+
+
+def phases_mode(B, wl, dev, buf):
+    """Where the time of mfma_big_kernel goes on config 1 and on the same outputs with K = 256: per-wave time stamps
+    (100 MHz clock) of an instrumented build, relative to the first wave's entry; min / mean / max over the 1024 waves."""
+    import numpy as np
+    import torch
+    out = {"mode": "phases", "unit": "us", "clock": "wall_clock64, 100 MHz"}
+    for K in (256, 4096):
+        W, X = wl.operand(1, 4096, K, 1, wl.ENC_PM1), wl.operand(2, 4096, K, 2, wl.ENC_UNSIGNED)
+        Wp, Xp = B.apnn_pack(dev(W), 1, wl.ENC_PM1), B.apnn_pack(dev(X), 2, wl.ENC_UNSIGNED)
+        Y = torch.empty((4096, 4096), dtype=torch.int32, device="cuda")
+        for _ in range(3):
+            B.apnn_gemm(Wp, Xp, 4096, 4096, K, 1, 2, wl.ENC_PM1, wl.ENC_UNSIGNED, out=Y)
+        torch.cuda.synchronize()
+        d = buf.cpu().numpy().reshape(256, 4, 8).astype(np.float64) * 0.01
+        if not d[:, :, 0].any():
+            sys.exit("bench.py --phases: no time stamps; build the library with -DAPNN_BIG_TIMING first")
+        base = d[:, :, 0].min()
+        st = lambda x: {"min": round(float(x.min()), 2), "mean": round(float(x.mean()), 2), "max": round(float(x.max()), 2)}
+        out[f"K{K}"] = {"entry": st(d[:, :, 0] - base), "entry_to_loop": st(d[:, :, 1] - d[:, :, 0]),
+                        "loop": st(d[:, :, 2] - d[:, :, 1]), "last_store_issued_after_loop": st(d[:, :, 3] - d[:, :, 2]),
+                        "stores_acknowledged_after_that": st(d[:, :, 4] - d[:, :, 3]),
+                        "loop_end_since_first_entry": st(d[:, :, 2] - base), "done_since_first_entry": st(d[:, :, 4] - base)}
+    print(json.dumps(out), flush=True)
 
 
 def evidence_mode(B, wl, dev):

@@ -461,6 +461,9 @@ extern "C" int apnn_gemm(const uint32_t *W_dev, const uint32_t *X_dev, int32_t *
     t.Kw = static_cast<int>(apnn_row_words(K));
     t.ldwA = t.ldwB = t.Kw;
     t.Y = Y_dev;
+#ifdef APNN_BIG_TIMING                              // instrumented build: where mfma_big_kernel leaves its time stamps (mfma_big.h)
+    if (const char *e = std::getenv("APNN_DBG_PTR")) t.T = reinterpret_cast<float *>(std::strtoull(e, nullptr, 0));
+#endif
     t.NW = static_cast<int>(N / 32);
     Problem pr{"apnn_gemm", false, M, N, K, p, q, encW, encX};
     return run_either(pr, t, 4, stream, nullptr);

@@ -138,6 +138,9 @@ __device__ __forceinline__ void expand_task(uint32_t x0, uint32_t x1, const Pair
 template <int KA, int KB, int NWM, int NWN, int FM, int FN>
 __global__ __launch_bounds__(64 * NWM * NWN, FM * FN >= 16 ? 1 : 2) void mfma_big_kernel(const MfmaParams p)
 {
+#ifdef APNN_BIG_TIMING                              // instrumented build (see the epilogue): time stamps of the 100 MHz clock
+    const unsigned long long tt0 = wall_clock64();
+#endif
     constexpr int KC = 16;                              // words per chunk = 8 matrix-instruction steps = 2 groups of 4
     constexpr int LA = DigitPlanes<KA>::value, LB = DigitPlanes<KB>::value;
     constexpr int BM = NWM * FM * 32, BN = NWN * FN * 32;
@@ -391,6 +394,9 @@ __global__ __launch_bounds__(64 * NWM * NWN, FM * FN >= 16 ? 1 : 2) void mfma_bi
         });
     });
 
+#ifdef APNN_BIG_TIMING
+    const unsigned long long tt1 = wall_clock64();
+#endif
     for (int it = 0; it < total_it; ++it) {
         const int buf = it & 1;
         int sa = 0x7f7f7f7f + 0x02020202 * cda + 0x01010101 * log2_out, sb = 0x7f7f7f7f + 0x02020202 * cdb;
@@ -416,6 +422,9 @@ __global__ __launch_bounds__(64 * NWM * NWN, FM * FN >= 16 ? 1 : 2) void mfma_bi
         advance(cda, cdb, ck);
     }
     __builtin_amdgcn_s_waitcnt(VMCNT0);                 // the loads issued for chunks beyond the last one have landed
+#ifdef APNN_BIG_TIMING
+    const unsigned long long tt2 = wall_clock64();
+#endif
 
     // ---- epilogue
     if (p.Y && !p.scale) {
@@ -441,6 +450,21 @@ __global__ __launch_bounds__(64 * NWM * NWN, FM * FN >= 16 ? 1 : 2) void mfma_bi
             __builtin_amdgcn_raw_buffer_store_b32(static_cast<int>(acc[i][j][r]) + p.c0, rsrcY,
                                                   voffY[j] + 4u * row * static_cast<uint32_t>(p.N), 0, 0);
         });
+#ifdef APNN_BIG_TIMING
+        // Instrumented build only (-DAPNN_BIG_TIMING, `python bench.py --phases`): every wave leaves the time stamps
+        // of its entry, the start and the end of its main loop, its last store instruction and the acknowledgement
+        // of its stores in the buffer that p.T points at (8 x 64 bits per wave; apnn_gemm takes the address from
+        // the environment variable APNN_DBG_PTR in such a build).
+        {
+            const unsigned long long tt3 = wall_clock64();
+            __builtin_amdgcn_s_waitcnt(0);              // all stores of this wave have been acknowledged
+            const unsigned long long tt4 = wall_clock64();
+            if (lane == 0 && p.T) {
+                unsigned long long *d = reinterpret_cast<unsigned long long *>(p.T) + (static_cast<size_t>(blockIdx.x) * NW + wave) * 8;
+                d[0] = tt0; d[1] = tt1; d[2] = tt2; d[3] = tt3; d[4] = tt4;
+            }
+        }
+#endif
         return;
     }
     MfmaParams pe = p;                                  // the scale is already in the accumulators
